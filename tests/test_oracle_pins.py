@@ -1,0 +1,306 @@
+"""Pins of the fp64 oracle against things other than itself (CPU only).
+
+Algorithm 1 of the paper is a definition; the paper prints no numbers for it.  So
+the oracle is pinned by (a) a hand-worked instance (tests/golden), (b) special cases
+in which the layer collapses to a textbook routine evaluated with numpy / scipy
+library calls, (c) numpy's stable sort for the selection and the permutation,
+(d) central finite differences of the oracle's own forward for every gradient, and
+(e) invariances.  Shapes are non-square (d != h != E) so a transposed operand fails.
+"""
+import os
+
+import numpy as np
+import pytest
+from scipy.special import softmax
+from scipy.stats import norm
+
+import oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "worked_example.txt")
+
+
+def _rand_problem(seed, N=7, d=5, h=6, E=4, k=2, bias=True, dy=True, dtype=np.float64):
+    g = np.random.default_rng(seed)
+    X = g.standard_normal((N, d))
+    Wg = g.standard_normal((d, E))
+    W1 = g.standard_normal((E, d, h)) * 0.7
+    W2 = g.standard_normal((E, h, d)) * 0.7
+    bg = g.standard_normal(E) * 0.3 if bias else None
+    dY = g.standard_normal((N, d)) if dy else None
+    c = lambda a: None if a is None else a.astype(dtype)
+    return orc.OracleProblem(c(X), c(Wg), c(W1), c(W2), k, bg=bg, dY=c(dY))
+
+
+def _gelu(z):          # z * Phi(z) through scipy's normal CDF (library routine, not erf)
+    return z * norm.cdf(z)
+
+
+def _gelu_grad(z):
+    return norm.cdf(z) + z * norm.pdf(z)
+
+
+def _ffn(x, W1, W2):
+    return _gelu(x @ W1) @ W2
+
+
+# ------------------------------------------------------------------ (a) hand-worked instance
+def _golden():
+    vals = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *nums = line.split()
+            vals[key] = np.array([float(v) for v in nums])
+    return vals
+
+
+def _worked_problem(k, dY=None):
+    X = np.array([[1.0, 2.0]])
+    Wg = np.eye(2)
+    W1 = np.array([[[1.0, 0.0], [0.0, 0.0]], [[0.0, 0.0], [0.5, -0.5]]])
+    W2 = np.array([[[2.0, 0.0], [0.0, 0.0]], [[1.0, 1.0], [0.0, 2.0]]])
+    return orc.OracleProblem(X, Wg, W1, W2, k, dY=dY)
+
+
+def test_worked_example_k2():
+    gold = _golden()
+    out = orc.layer(_worked_problem(2, dY=np.array([[1.0, 0.0]])), want_internals=True)
+    assert out["idx"].tolist() == [gold["idx_k2"].astype(int).tolist()]
+    np.testing.assert_allclose(out["w"][0], gold["w_k2"], rtol=0, atol=2e-16)
+    np.testing.assert_allclose(out["Z"][0, 0], gold["z_slot0"], rtol=0, atol=0)
+    np.testing.assert_allclose(out["Z"][0, 1], gold["z_slot1"], rtol=0, atol=0)
+    np.testing.assert_allclose(out["O"][0, 0], gold["o_slot0"], rtol=0, atol=3e-16)
+    np.testing.assert_allclose(out["O"][0, 1], gold["o_slot1"], rtol=0, atol=3e-16)
+    np.testing.assert_allclose(out["Y"][0], gold["y_k2"], rtol=0, atol=5e-16)
+    np.testing.assert_allclose(out["dl"][0], gold["dl_k2"], rtol=0, atol=5e-16)
+
+
+def test_worked_example_k1():
+    gold = _golden()
+    out = orc.layer(_worked_problem(1))
+    assert out["idx"].tolist() == [[1]]
+    assert out["w"][0, 0] == 1.0
+    np.testing.assert_allclose(out["Y"][0], gold["y_k1"], rtol=0, atol=3e-16)
+
+
+# ------------------------------------------------------------------ (b) collapses to textbook routines
+def test_single_expert_is_dense_ffn_forward_and_backward():
+    p = _rand_problem(1, N=9, d=5, h=7, E=1, k=1)
+    out = orc.layer(p)
+    X, W1, W2, dY = p.X, p.W1[0], p.W2[0], p.dY
+    Z = X @ W1
+    G = _gelu(Z)
+    np.testing.assert_allclose(out["Y"], G @ W2, rtol=1e-12, atol=1e-13)
+    assert np.all(out["w"] == 1.0) and np.all(out["idx"] == 0)
+    dG = dY @ W2.T
+    dZ = dG * _gelu_grad(Z)
+    np.testing.assert_allclose(out["dW2"][0], G.T @ dY, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out["dW1"][0], X.T @ dZ, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out["dX"], dZ @ W1.T, rtol=1e-12, atol=1e-12)   # gate term is 0 for k=1
+    assert np.all(out["dl"] == 0.0) and np.all(out["dWg"] == 0.0) and np.all(out["dbg"] == 0.0)
+
+
+def test_k_equals_E_is_dense_softmax_mixture():
+    p = _rand_problem(2, N=6, d=4, h=5, E=3, k=3, dy=False)
+    out = orc.layer(p)
+    logits = p.X @ p.Wg + p.bg
+    prob = softmax(logits, axis=1)
+    ref = sum(prob[:, [e]] * _ffn(p.X, p.W1[e], p.W2[e]) for e in range(p.E))
+    np.testing.assert_allclose(out["Y"], ref, rtol=1e-12, atol=1e-13)
+    # slots are in descending-logit order and the weights are the softmax probabilities
+    np.testing.assert_array_equal(out["idx"], np.argsort(-logits, axis=1, kind="stable"))
+    np.testing.assert_allclose(out["w"], -np.sort(-prob, axis=1), rtol=1e-13)
+
+
+def test_identical_experts_make_the_gate_irrelevant():
+    p0 = _rand_problem(3, N=8, d=4, h=6, E=5, k=3)
+    W1 = np.repeat(p0.W1[:1], p0.E, axis=0)
+    W2 = np.repeat(p0.W2[:1], p0.E, axis=0)
+    p = orc.OracleProblem(p0.X, p0.Wg, W1, W2, 3, bg=p0.bg, dY=p0.dY)
+    out = orc.layer(p)
+    np.testing.assert_allclose(out["Y"], _ffn(p.X, W1[0], W2[0]), rtol=1e-12, atol=1e-13)
+    # sum over experts of dW equals the dense FFN weight gradient
+    Z = p.X @ W1[0]
+    dZ = (p.dY @ W2[0].T) * _gelu_grad(Z)
+    np.testing.assert_allclose(out["dW1"].sum(0), p.X.T @ dZ, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(out["dW2"].sum(0), _gelu(Z).T @ p.dY, rtol=1e-11, atol=1e-12)
+    # every expert gives the same output, so dL/dw_j are equal and the softmax passes no gradient
+    np.testing.assert_allclose(out["dl"], 0.0, atol=1e-13)
+
+
+def test_output_is_linear_in_W2():
+    p = _rand_problem(4, dy=False)
+    y = orc.layer(p)["Y"]
+    y3 = orc.layer(orc.OracleProblem(p.X, p.Wg, p.W1, -3.0 * p.W2, p.k, bg=p.bg))["Y"]
+    y0 = orc.layer(orc.OracleProblem(p.X, p.Wg, p.W1, 0.0 * p.W2, p.k, bg=p.bg))["Y"]
+    np.testing.assert_allclose(y3, -3.0 * y, rtol=1e-13, atol=1e-14)
+    assert np.all(y0 == 0.0)
+
+
+def test_top1_of_two_experts_selects_by_sign():
+    # E=2,k=1 with Wg = (+v, -v): expert 0 iff <x,v> >= 0 (tie -> lower id); output is that expert's FFN
+    g = np.random.default_rng(5)
+    X = g.standard_normal((20, 3))
+    X[3] = 0.0                                        # exact tie
+    v = g.standard_normal(3)
+    Wg = np.stack([v, -v], axis=1)
+    W1 = g.standard_normal((2, 3, 4))
+    W2 = g.standard_normal((2, 4, 3))
+    out = orc.layer(orc.OracleProblem(X, Wg, W1, W2, 1))
+    sel = np.where(X @ v >= 0, 0, 1)
+    np.testing.assert_array_equal(out["idx"][:, 0], sel)
+    ref = np.stack([_ffn(X[t], W1[sel[t]], W2[sel[t]]) for t in range(20)])
+    np.testing.assert_allclose(out["Y"], ref, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ (c) selection and permutation
+def test_topk_matches_numpy_stable_sort_with_engineered_ties():
+    g = np.random.default_rng(6)
+    N, d, E, k = 64, 6, 9, 4
+    X = g.integers(-3, 4, (N, d)).astype(np.float64)      # small integers: all sums exact, many ties
+    Wg = g.integers(-2, 3, (d, E)).astype(np.float64)
+    Wg[:, 5] = Wg[:, 2]                                   # duplicate columns: exact ties everywhere
+    Wg[:, 7] = Wg[:, 0]
+    X[10] = 0.0                                           # all logits equal -> 0,1,2,3
+    W1 = np.zeros((E, d, 2))
+    W2 = np.zeros((E, 2, d))
+    p = orc.OracleProblem(X, Wg, W1, W2, k)
+    idx, w, logits = orc.gate(p)
+    np.testing.assert_array_equal(logits, X @ Wg)
+    ref = np.argsort(-logits, axis=1, kind="stable")[:, :k]
+    np.testing.assert_array_equal(idx, ref)
+    assert idx[10].tolist() == [0, 1, 2, 3]
+    sel = np.take_along_axis(logits, ref, axis=1)
+    np.testing.assert_allclose(w, softmax(sel, axis=1), rtol=1e-14)
+    np.testing.assert_allclose(w.sum(1), 1.0, atol=1e-15)
+    assert np.all(np.diff(w, axis=1) <= 0) and np.all(w > 0)
+    assert all(len(set(r)) == k for r in idx.tolist())
+
+
+def test_gate_bias_enters_the_logits():
+    p = _rand_problem(7, N=12, d=5, E=6, k=2, dy=False)
+    idx, w, logits = orc.gate(p)
+    np.testing.assert_allclose(logits, p.X @ p.Wg + p.bg, rtol=1e-13, atol=1e-14)
+
+
+def test_plan_is_numpy_stable_counting_sort():
+    g = np.random.default_rng(8)
+    E, N, k = 7, 500, 2
+    idx = g.integers(0, E, (N, k)).astype(np.int32)
+    idx[idx == 4] = 3                                      # expert 4 stays empty
+    counts, offsets, pos, perm = orc.plan(idx, E)
+    flat = idx.reshape(-1)
+    np.testing.assert_array_equal(counts, np.bincount(flat, minlength=E))
+    np.testing.assert_array_equal(offsets, np.concatenate([[0], np.cumsum(counts)]))
+    np.testing.assert_array_equal(perm, np.argsort(flat, kind="stable"))
+    np.testing.assert_array_equal(perm[pos], np.arange(N * k))           # bijection
+    assert counts[4] == 0 and counts.sum() == N * k and offsets[-1] == N * k
+    for e in range(E):
+        seg = perm[offsets[e]:offsets[e + 1]]
+        assert np.all(flat[seg] == e) and np.all(np.diff(seg) > 0)
+
+
+def test_plan_rejects_out_of_range_expert():
+    with pytest.raises(ValueError):
+        orc.plan(np.array([[0, 5]], np.int32), 4)
+
+
+# ------------------------------------------------------------------ (d) gradients by finite differences
+def _loss(p):
+    return float((orc.layer(orc.OracleProblem(p.X, p.Wg, p.W1, p.W2, p.k, bg=p.bg))["Y"] * p.dY).sum())
+
+
+@pytest.mark.parametrize("k,E", [(2, 4), (1, 3), (3, 3)])
+def test_gradients_match_central_differences(k, E):
+    for seed in range(40, 60):
+        p = _rand_problem(seed, N=4, d=3, h=5, E=E, k=k)
+        _, _, logits = orc.gate(p)
+        srt = -np.sort(-logits, axis=1)
+        if k == E or np.min(srt[:, :k] - srt[:, 1:k + 1]) > 5e-2:       # selection locally constant
+            break
+    else:
+        pytest.skip("no seed with a safe decision gap")
+    out = orc.layer(p)
+    eps = 1e-6
+    for name, grad in (("X", out["dX"]), ("Wg", out["dWg"]), ("bg", out["dbg"]),
+                       ("W1", out["dW1"]), ("W2", out["dW2"])):
+        arr = getattr(p, name)
+        num = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            old = arr[i]
+            arr[i] = old + eps
+            lp = _loss(p)
+            arr[i] = old - eps
+            lm = _loss(p)
+            arr[i] = old
+            num[i] = (lp - lm) / (2 * eps)
+        scale = max(1.0, np.abs(num).max())
+        assert np.max(np.abs(num - grad)) / scale < 2e-8, name
+        if k > 1 and name in ("Wg", "bg"):
+            assert np.abs(grad).max() > 1e-3          # the gate really receives gradient via the score
+
+
+def test_k1_passes_no_gradient_to_the_gate():
+    out = orc.layer(_rand_problem(9, k=1))
+    assert np.all(out["dl"] == 0) and np.all(out["dWg"] == 0) and np.all(out["dbg"] == 0)
+
+
+# ------------------------------------------------------------------ (e) invariances and API consistency
+def test_token_permutation_equivariance_and_expert_relabelling():
+    p = _rand_problem(10, N=10, d=4, h=5, E=4, k=2)
+    out = orc.layer(p)
+    g = np.random.default_rng(0)
+    tp = g.permutation(p.N)
+    q = orc.OracleProblem(p.X[tp], p.Wg, p.W1, p.W2, p.k, bg=p.bg, dY=p.dY[tp])
+    oq = orc.layer(q)
+    np.testing.assert_allclose(oq["Y"], out["Y"][tp], rtol=0, atol=0)
+    np.testing.assert_allclose(oq["dX"], out["dX"][tp], rtol=0, atol=0)
+    np.testing.assert_allclose(oq["dW1"], out["dW1"], rtol=1e-12, atol=1e-13)
+    ep = np.array([2, 0, 3, 1])                               # new expert e' holds old expert ep[e']
+    r = orc.OracleProblem(p.X, p.Wg[:, ep], p.W1[ep], p.W2[ep], p.k, bg=p.bg[ep], dY=p.dY)
+    orr = orc.layer(r)
+    np.testing.assert_allclose(orr["Y"], out["Y"], rtol=1e-13, atol=1e-14)
+    np.testing.assert_array_equal(ep[orr["idx"]], out["idx"])
+    np.testing.assert_allclose(orr["dW2"], out["dW2"][ep], rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(orr["dWg"], out["dWg"][:, ep], rtol=1e-13, atol=1e-14)
+
+
+def test_storage_types_are_widened_exactly():
+    from paper_2103_13262_amd.synth import f32_to_bf16_bits, bf16_bits_to_f32
+
+    g = np.random.default_rng(11)
+    mk = lambda *s: g.standard_normal(s).astype(np.float32)
+    X, Wg, W1, W2, dY = mk(6, 8), mk(8, 3), mk(3, 8, 4), mk(3, 4, 8), mk(6, 8)
+    bits = [f32_to_bf16_bits(a) for a in (X, Wg, W1, W2, dY)]
+    wide = [orc.bf16_bits_to_f64(b) for b in bits]
+    for b, wd in zip(bits, wide):
+        np.testing.assert_array_equal(bf16_bits_to_f32(b).astype(np.float64), wd)
+    ob = orc.layer(orc.OracleProblem(*bits[:4], 2, dY=bits[4]))
+    ow = orc.layer(orc.OracleProblem(*wide[:4], 2, dY=wide[4]))
+    of = orc.layer(orc.OracleProblem(*[a.astype(np.float32) for a in wide[:4]], 2, dY=wide[4].astype(np.float32)))
+    for key in ("Y", "dX", "dW1", "dW2", "dWg", "dbg", "w"):
+        np.testing.assert_array_equal(ob[key], ow[key])
+        np.testing.assert_array_equal(of[key], ow[key])
+    # bf16 rounding itself: round-to-nearest-even on a half-way case and a plain case
+    assert f32_to_bf16_bits(np.array([1.00390625], np.float32))[0] == 0x3F80      # tie -> even
+    assert f32_to_bf16_bits(np.array([1.01171875], np.float32))[0] == 0x3F82      # tie -> even (up)
+    assert f32_to_bf16_bits(np.array([-2.5], np.float32))[0] == 0xC020
+
+
+def test_token_subsets_and_tracked_experts_are_consistent():
+    p = _rand_problem(12, N=12, d=4, h=5, E=4, k=2)
+    full = orc.layer(p)
+    a, b = np.array([0, 3, 4, 9, 11], np.int32), np.array([1, 2, 5, 6, 7, 8, 10], np.int32)
+    oa, ob = orc.layer(p, tokens=a), orc.layer(p, tokens=b)
+    np.testing.assert_array_equal(oa["Y"], full["Y"][a])
+    np.testing.assert_array_equal(ob["dX"], full["dX"][b])
+    np.testing.assert_allclose(oa["dW1"] + ob["dW1"], full["dW1"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(oa["dWg"] + ob["dWg"], full["dWg"], rtol=1e-12, atol=1e-13)
+    trk = np.array([2, 0], np.int32)
+    ot = orc.layer(p, track=trk, only_tracked=True)
+    np.testing.assert_array_equal(ot["dW1"], full["dW1"][trk])
+    np.testing.assert_array_equal(ot["dW2"], full["dW2"][trk])
+    assert "Y" not in ot and "dWg" not in ot
