@@ -1,0 +1,139 @@
+/*
+ * moe355.h -- C ABI of libmoe355: one Mixture-of-Experts layer with top-k gating,
+ * forward and backward, on one AMD MI355X (gfx950).
+ *
+ * What the layer computes is Algorithm 1 of the FastMoE paper ("Forward computation
+ * of an MoE layer with top-k gating") for every row x of X:
+ *
+ *     score = G(x);  indices = ArgMax_k(score);  y = sum_{i in indices} score_i * E_i(x)
+ *
+ * with the notation of the paper's Section 5.1: n_b = N input samples, n_e = E experts
+ * (all on this GPU), each expert two linear layers of sizes d_m x d_h and d_h x d_m
+ * (d and h here), top-k selection.  The gate G is one fully-connected layer (Section
+ * 5.2).  How it is computed is the reordering of the paper's Section 4: the samples
+ * of one expert are placed in a contiguous buffer ("scatter"), each expert processes
+ * its batch as matrix products, and the rows are put back in their original order
+ * ("gather"); the per-expert sample counts are taken first and fix the buffer layout
+ * (Section 3.2, description of the global operations figure).
+ *
+ * Points on which the paper is silent and this library fixes a reading:
+ *   logits l = x W_g + b_g;  top-k on the logits, equal logits -> lower expert id,
+ *   slot j = j-th largest;  score = softmax over the k selected logits;
+ *   E_e(x) = GeLU(x W1[e]) W2[e] with the erf GeLU and no expert biases;
+ *   inside an expert's segment rows keep assignment order a = t*k + j;
+ *   backward = gradient of <dY, Y> with the selected indices held constant.
+ *
+ * All matrices are dense row-major.  Every pointer named "device" must be device
+ * memory of the current HIP device, 16-byte aligned, owned by the caller for the
+ * whole call and until the stream work has completed.  The library allocates
+ * nothing, keeps no pointer after a call returns and has no global state besides
+ * the thread-local error string.  All work is enqueued on `stream` (a hipStream_t
+ * passed as void*, NULL = the null stream); no call synchronises with the host or
+ * copies anything to the host.  Calls return a status; nothing throws or aborts.
+ */
+#ifndef MOE355_H
+#define MOE355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = -1, /* null required pointer, misaligned pointer, N<0, k<1, k>E, ...  */
+    MOE_ERR_UNSUPPORTED = -2, /* d or h not a multiple of 32, E>1024, k>8, unknown dtype,
+                                 non-zero reserved field, expert bias given                  */
+    MOE_ERR_WORKSPACE = -3,   /* workspace smaller than moe_workspace_bytes()                 */
+    MOE_ERR_HIP = -4          /* a kernel launch reported an error                            */
+} moe_status_t;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+
+/* Problem description; plain host struct passed by pointer. */
+typedef struct {
+    int32_t N;          /* n_b: rows of X (tokens); 0 is allowed (nothing is launched)        */
+    int32_t d;          /* d_m: model width, multiple of 32                                   */
+    int32_t h;          /* d_h: expert hidden width, multiple of 32                           */
+    int32_t E;          /* n_e: experts, 1..1024                                              */
+    int32_t k;          /* experts selected per token, 1..min(E,8)                            */
+    int32_t dtype;      /* moe_dtype_t of X, W_g, W1, W2, Y, dY, dX and the saved activations */
+    int32_t grad_dtype; /* moe_dtype_t of dW1, dW2, dW_g: equal to dtype, or MOE_F32          */
+    int32_t accumulate; /* 0: weight gradients are overwritten (zeros for an expert that got
+                           no row); 1: added to what the buffers hold                         */
+    int32_t reserved[8]; /* must be zero                                                      */
+} moe_desc_t;
+
+/* Routing of one batch; six caller-owned device arrays that moe_plan fills and
+ * moe_forward / moe_backward read.  M = N*k assignments, a = t*k + j. */
+typedef struct {
+    int32_t *topk_idx; /* [N,k] expert of slot j of token t, slots in descending logit order  */
+    float *topk_w;     /* [N,k] combine weight (score) of that slot; each row sums to 1       */
+    int32_t *counts;   /* [E]   rows received by each expert                                  */
+    int32_t *offsets;  /* [E+1] exclusive prefix sum of counts; offsets[E] = M                */
+    int32_t *pos;      /* [M]   assignment a -> row of the expert-contiguous buffers          */
+    int32_t *perm;     /* [M]   row of the expert-contiguous buffers -> assignment a          */
+} moe_plan_t;
+
+/* Bytes of device workspace the three calls below need for this problem (expert-contiguous
+ * activations Xs, Z, H, Ys, their gradients, the tile schedule and reduction scratch).
+ * Returns 0 if desc is NULL or not supported. Host-only; touches no device. */
+size_t moe_workspace_bytes(const moe_desc_t *desc);
+
+/*
+ * Gate, selection, counting and layout (Algorithm 1 steps "score" and "indices"; the
+ * count / offset step of Section 3.2).
+ *   X  device [N,d] dtype;  Wg device [d,E] dtype;  bg device [E] float or NULL (= zeros).
+ *   plan: host struct holding six device arrays, all written.
+ *   workspace: device, >= moe_workspace_bytes(); the tile schedule written here is read by
+ *   moe_forward / moe_backward, which must receive the same workspace.
+ * The selection is exact: logits are accumulated in fp64, so indices, counts and the
+ * permutation are those of exact arithmetic unless two logits agree to ~1e-15 relative.
+ */
+moe_status_t moe_plan(const moe_desc_t *desc, const void *X, const void *Wg, const float *bg,
+                      moe_plan_t *plan, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Forward: scatter, per-expert FFN as grouped matrix products, weighted gather
+ * (Section 4 reordering of Algorithm 1's loop).
+ *   W1 device [E,d,h], W2 device [E,h,d] dtype;  b1, b2 must be NULL (expert biases unsupported).
+ *   Y device [N,d] dtype, written.
+ * Leaves Xs, Z (pre-activation), H = GeLU(Z) and Ys in the workspace for moe_backward.
+ */
+moe_status_t moe_forward(const moe_desc_t *desc, const moe_plan_t *plan, const void *X, const void *W1,
+                         const void *W2, const void *b1, const void *b2, void *Y, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/*
+ * Backward of L = <dY, Y> (the paper states that forward and backward both run through
+ * the same reordering, Section 3.2, and that the gate is trained through the score,
+ * Section 2.1).  Must follow moe_forward on the same desc, plan and untouched workspace.
+ *   dY device [N,d] dtype.
+ *   dX device [N,d] dtype, written (expert path + gate path).
+ *   dWg device [d,E], dW1 device [E,d,h], dW2 device [E,h,d] in grad_dtype; written or
+ *   accumulated per desc->accumulate.  dbg device [E] float or NULL, same rule.
+ * Weight gradients are reduced in a fixed order: repeated calls give identical bits.
+ */
+moe_status_t moe_backward(const moe_desc_t *desc, const moe_plan_t *plan, const void *X, const void *Wg,
+                          const void *W1, const void *W2, const void *dY, void *dX, void *dWg, float *dbg,
+                          void *dW1, void *dW2, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Where a named intermediate lives inside the workspace (host-only; touches no device).
+ * Names: "Xs" [M,d] scattered inputs, "Z" [M,h] pre-activations, "H" [M,h] GeLU(Z), "Ys" [M,d]
+ * expert outputs before the weighted gather (these four are valid after moe_forward);
+ * "dYs" [M,d], "dZ" [M,h], "dXs" [M,d] (dtype elements) and "dl" [M] float, the gradient of the
+ * selected logits (valid after moe_backward).  Rows are in expert-contiguous order (row r holds
+ * assignment perm[r]).  Returns MOE_ERR_INVALID_ARG for an unknown name.
+ */
+moe_status_t moe_workspace_region(const moe_desc_t *desc, const char *name, size_t *offset, size_t *bytes);
+
+/* Text of the last error on this thread ("" if none). Static storage; do not free. */
+const char *moe_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE355_H */

@@ -1,0 +1,136 @@
+// Shared host/device declarations of libmoe355 (internal; the public ABI is include/moe355.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/moe355.h"
+
+namespace moe {
+
+constexpr int kMaxE = 1024;
+constexpr int kMaxK = 8;
+constexpr int kPlanChunk = 1024;  // assignments ranked by one workgroup of the plan kernels
+constexpr int kNumTileHeights = 4;  // row-tile prefix tables are kept for 32, 64, 128, 256 rows
+__host__ __device__ constexpr int tile_height(int q) { return 32 << q; }
+__host__ __device__ constexpr int tile_height_index(int bm) { return bm == 32 ? 0 : bm == 64 ? 1 : bm == 128 ? 2 : 3; }
+
+// ---- workspace layout (byte offsets from the workspace base; every region 256-B aligned) ----
+struct WsLayout {
+    size_t Xs, Z, H, Ys, dYs, dZ, dXs;  // expert-contiguous activations / gradients, element type = desc.dtype
+    size_t dl;        // [M]  float: gradient of the selected logits, by assignment
+    size_t tileP;     // [4][E+1] int32: prefix of ceil(counts/BM) for BM = 32,64,128,256
+    size_t order;     // [E] int32: experts by descending count (ties: lower id first)
+    size_t hist;      // [nb][E] int32: per plan-chunk histogram, then exclusive base inside the expert
+    size_t dwg_part;  // [E][S][d] float: partial sums of dWg
+    size_t dbg_part;  // [E][S] float
+    size_t total;
+    int nb;           // plan chunks = ceil(M / kPlanChunk)
+    int S;            // row splits per expert for the dWg reduction
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t dtype_size(int dt) { return dt == MOE_BF16 ? 2 : 4; }
+
+inline int dwg_splits(const moe_desc_t& D)
+{
+    long M = (long)D.N * D.k;
+    long avg = D.E > 0 ? M / D.E : 0;
+    long s = (avg + 31) / 32;
+    if (s < 1) s = 1;
+    if (s > 32) s = 32;
+    return (int)s;
+}
+
+inline WsLayout ws_layout(const moe_desc_t& D)
+{
+    WsLayout L{};
+    const size_t M = (size_t)D.N * D.k, b = dtype_size(D.dtype);
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.Xs = take(M * D.d * b);
+    L.Z = take(M * D.h * b);
+    L.H = take(M * D.h * b);
+    L.Ys = take(M * D.d * b);
+    L.dYs = take(M * D.d * b);
+    L.dZ = take(M * D.h * b);
+    L.dXs = take(M * D.d * b);
+    L.dl = take(M * sizeof(float));
+    L.tileP = take((size_t)kNumTileHeights * (D.E + 1) * sizeof(int32_t));
+    L.order = take((size_t)D.E * sizeof(int32_t));
+    L.nb = (int)((M + kPlanChunk - 1) / kPlanChunk);
+    L.hist = take((size_t)(L.nb > 0 ? L.nb : 1) * D.E * sizeof(int32_t));
+    L.S = dwg_splits(D);
+    L.dwg_part = take((size_t)D.E * L.S * D.d * sizeof(float));
+    L.dbg_part = take((size_t)D.E * L.S * sizeof(float));
+    L.total = o;
+    return L;
+}
+
+// ---- error reporting -------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+moe_status_t check_launch(const char* what);
+
+// ---- kernel launchers (each enqueues on `st`; operand shapes are validated by the callers) ----
+void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
+                      float* topk_w, hipStream_t st);
+void launch_plan(const moe_desc_t& D, const WsLayout& L, const int32_t* topk_idx, int32_t* counts,
+                 int32_t* offsets, int32_t* pos, int32_t* perm, char* ws, hipStream_t st);
+
+void launch_scatter(const moe_desc_t& D, const void* X, const int32_t* perm, void* Xs, hipStream_t st);
+void launch_combine(const moe_desc_t& D, const void* Ys, const float* topk_w, const int32_t* pos, void* Y,
+                    hipStream_t st);
+void launch_dcombine(const moe_desc_t& D, const void* dY, const void* Ys, const float* topk_w,
+                     const int32_t* pos, void* dYs, float* dl, hipStream_t st);
+void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, const void* dXs, const void* Wg,
+                     const float* dl, const int32_t* topk_idx, const int32_t* pos, const int32_t* perm,
+                     const int32_t* counts, const int32_t* offsets, void* dX, void* dWg, float* dbg, char* ws,
+                     hipStream_t st);
+
+// Grouped matrix products over the expert segments.
+//   kRows*: C[r,:] (r in segment e) = A[r,:] * op(B[e]);  A is [M,K] row-major, C is [M,Nout] row-major.
+//   kColsT: C[e] (K1 x K2) = A[seg e]^T * B[seg e];       A is [M,K1], B is [M,K2], C is [E,K1,K2].
+enum GemmKind {
+    kRowsNN_GeLU = 0,  // B[e] is [K,Nout];  writes C = acc (pre-activation) and C2 = GeLU(acc)
+    kRowsNN = 1,       // B[e] is [K,Nout]
+    kRowsNT_dGeLU = 2, // B[e] is [Nout,K];  C = acc * GeLU'(Zin)
+    kRowsNT = 3,       // B[e] is [Nout,K]
+    kColsT = 4         // weight gradient; honours grad_dtype and accumulate
+};
+struct GemmArgs {
+    int kind;
+    const void* A;
+    const void* B;
+    void* C;
+    void* C2;         // kRowsNN_GeLU: GeLU output
+    const void* Zin;  // kRowsNT_dGeLU: saved pre-activation [M,Nout]
+    int K;            // kRows*: reduction width;  kColsT: K1 (rows of C[e])
+    int Nout;         // kRows*: columns of C;     kColsT: K2 (columns of C[e])
+    long M;           // total rows (N*k)
+    int E;
+    const int32_t* counts;
+    const int32_t* offsets;
+    const int32_t* tileP;  // [4][E+1]
+    const int32_t* order;  // [E]
+    int out_f32;      // kColsT: C holds float (else the activation type)
+    int accumulate;   // kColsT
+};
+void launch_ggemm_f32(const GemmArgs& a, hipStream_t st);
+void launch_ggemm_bf16(const GemmArgs& a, hipStream_t st);
+
+// ---- small device helpers ------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }
+__device__ __forceinline__ unsigned short f32_to_bf16(float f)
+{
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);                                                  // round to nearest even
+    return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float z)
+{
+    return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * __expf(-0.5f * z * z) * 0.39894228040143268f;
+}
+
+}  // namespace moe

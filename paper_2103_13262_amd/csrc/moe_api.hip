@@ -1,0 +1,266 @@
+// C ABI of libmoe355 (declared in include/moe355.h): argument checks on the host, then the
+// kernels of one MoE layer enqueued on the caller's stream in the order of the paper's reordered
+// computation (Section 4): gate + top-k (Algorithm 1), count/offsets (Section 3.2), scatter,
+// per-expert linear layers as grouped products, gather; and the reverse for the gradient.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+
+namespace moe {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+moe_status_t check_launch(const char* what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("%s: %s", what, hipGetErrorString(e));
+        return MOE_ERR_HIP;
+    }
+    return MOE_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static moe_status_t check_desc(const moe_desc_t* D)
+{
+    if (!D) { set_error("desc is NULL"); return MOE_ERR_INVALID_ARG; }
+    if (D->N < 0 || D->d < 1 || D->h < 1 || D->E < 1 || D->k < 1 || D->k > D->E) {
+        set_error("invalid sizes N=%d d=%d h=%d E=%d k=%d (need N>=0, d,h,E>=1, 1<=k<=E)", D->N, D->d, D->h, D->E, D->k);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (D->accumulate != 0 && D->accumulate != 1) { set_error("accumulate must be 0 or 1"); return MOE_ERR_INVALID_ARG; }
+    if (D->dtype != MOE_F32 && D->dtype != MOE_BF16) { set_error("unknown dtype %d", D->dtype); return MOE_ERR_UNSUPPORTED; }
+    if (D->grad_dtype != D->dtype && D->grad_dtype != MOE_F32) {
+        set_error("grad_dtype %d unsupported with dtype %d (must equal dtype or be fp32)", D->grad_dtype, D->dtype);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (D->d % 32 || D->h % 32) { set_error("d=%d and h=%d must be multiples of 32", D->d, D->h); return MOE_ERR_UNSUPPORTED; }
+    if (D->E > kMaxE) { set_error("E=%d exceeds %d", D->E, kMaxE); return MOE_ERR_UNSUPPORTED; }
+    if (D->k > kMaxK) { set_error("k=%d exceeds %d", D->k, kMaxK); return MOE_ERR_UNSUPPORTED; }
+    for (int i = 0; i < 8; ++i)
+        if (D->reserved[i]) { set_error("reserved[%d] must be 0", i); return MOE_ERR_UNSUPPORTED; }
+    const long long M = (long long)D->N * D->k;
+    if (M > 0x7fffffffLL || M * (long long)(D->d > D->h ? D->d : D->h) > (1LL << 46)) {
+        set_error("problem too large: N*k=%lld", M);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    return MOE_OK;
+}
+
+#define MOE_REQUIRE_PTR(p)                                                               \
+    do {                                                                                 \
+        if (!(p)) { set_error(#p " is NULL"); return MOE_ERR_INVALID_ARG; }              \
+        if (!aligned16(p)) { set_error(#p " is not 16-byte aligned"); return MOE_ERR_INVALID_ARG; } \
+    } while (0)
+
+static moe_status_t check_plan(const moe_plan_t* P)
+{
+    if (!P) { set_error("plan is NULL"); return MOE_ERR_INVALID_ARG; }
+    MOE_REQUIRE_PTR(P->topk_idx);
+    MOE_REQUIRE_PTR(P->topk_w);
+    MOE_REQUIRE_PTR(P->counts);
+    MOE_REQUIRE_PTR(P->offsets);
+    MOE_REQUIRE_PTR(P->pos);
+    MOE_REQUIRE_PTR(P->perm);
+    return MOE_OK;
+}
+
+static moe_status_t check_ws(const moe_desc_t* D, const void* ws, size_t bytes, WsLayout* L)
+{
+    MOE_REQUIRE_PTR(ws);
+    *L = ws_layout(*D);
+    if (bytes < L->total) {
+        set_error("workspace too small: %zu bytes given, %zu needed", bytes, L->total);
+        return MOE_ERR_WORKSPACE;
+    }
+    return MOE_OK;
+}
+
+static void run_gemm(const moe_desc_t& D, GemmArgs& a, hipStream_t st)
+{
+    if (D.dtype == MOE_BF16) launch_ggemm_bf16(a, st);
+    else launch_ggemm_f32(a, st);
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+size_t moe_workspace_bytes(const moe_desc_t* desc)
+{
+    if (check_desc(desc) != MOE_OK) return 0;
+    return ws_layout(*desc).total;
+}
+
+const char* moe_last_error(void) { return g_err; }
+
+moe_status_t moe_workspace_region(const moe_desc_t* desc, const char* name, size_t* offset, size_t* bytes)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if (!name || !offset || !bytes) { set_error("name, offset and bytes must not be NULL"); return MOE_ERR_INVALID_ARG; }
+    const WsLayout L = ws_layout(*desc);
+    const size_t M = (size_t)desc->N * desc->k, b = dtype_size(desc->dtype);
+    const struct { const char* n; size_t off, len; } regions[] = {
+        {"Xs", L.Xs, M * desc->d * b}, {"Z", L.Z, M * desc->h * b},     {"H", L.H, M * desc->h * b},
+        {"Ys", L.Ys, M * desc->d * b}, {"dYs", L.dYs, M * desc->d * b}, {"dZ", L.dZ, M * desc->h * b},
+        {"dXs", L.dXs, M * desc->d * b}, {"dl", L.dl, M * sizeof(float)},
+    };
+    for (const auto& r : regions)
+        if (!strcmp(r.n, name)) { *offset = r.off; *bytes = r.len; return MOE_OK; }
+    set_error("unknown workspace region '%s'", name);
+    return MOE_ERR_INVALID_ARG;
+}
+
+moe_status_t moe_plan(const moe_desc_t* desc, const void* X, const void* Wg, const float* bg, moe_plan_t* plan,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    MOE_REQUIRE_PTR(X);
+    MOE_REQUIRE_PTR(Wg);
+    if (bg && (reinterpret_cast<uintptr_t>(bg) & 3u)) { set_error("bg is not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    WsLayout L;
+    if ((s = check_ws(desc, workspace, workspace_bytes, &L)) != MOE_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    const moe_desc_t& D = *desc;
+    if (D.N > 0) {
+        launch_gate_topk(D, X, Wg, bg, plan->topk_idx, plan->topk_w, st);
+        if ((s = check_launch("gate/top-k")) != MOE_OK) return s;
+    }
+    // With N == 0 the plan kernels still run: they write counts = 0, offsets = 0 and empty tile tables.
+    launch_plan(D, L, plan->topk_idx, plan->counts, plan->offsets, plan->pos, plan->perm, (char*)workspace, st);
+    return check_launch("plan");
+}
+
+moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const void* X, const void* W1,
+                         const void* W2, const void* b1, const void* b2, void* Y, void* workspace,
+                         size_t workspace_bytes, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    MOE_REQUIRE_PTR(X);
+    MOE_REQUIRE_PTR(W1);
+    MOE_REQUIRE_PTR(W2);
+    if (b1 || b2) { set_error("expert biases are not supported (b1 and b2 must be NULL)"); return MOE_ERR_UNSUPPORTED; }
+    WsLayout L;
+    if ((s = check_ws(desc, workspace, workspace_bytes, &L)) != MOE_OK) return s;
+    const moe_desc_t& D = *desc;
+    if (D.N == 0) return MOE_OK;
+    MOE_REQUIRE_PTR(Y);
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+
+    launch_scatter(D, X, plan->perm, ws + L.Xs, st);
+    if ((s = check_launch("scatter")) != MOE_OK) return s;
+
+    GemmArgs a{};
+    a.M = (long)D.N * D.k;
+    a.E = D.E;
+    a.counts = plan->counts;
+    a.offsets = plan->offsets;
+    a.tileP = (const int32_t*)(ws + L.tileP);
+    a.order = (const int32_t*)(ws + L.order);
+
+    a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
+    a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h;
+    run_gemm(D, a, st);
+    if ((s = check_launch("expert layer 1")) != MOE_OK) return s;
+
+    a.kind = kRowsNN;       // Ys = H W2[e]
+    a.A = ws + L.H; a.B = W2; a.C = ws + L.Ys; a.C2 = nullptr; a.K = D.h; a.Nout = D.d;
+    run_gemm(D, a, st);
+    if ((s = check_launch("expert layer 2")) != MOE_OK) return s;
+
+    launch_combine(D, ws + L.Ys, plan->topk_w, plan->pos, Y, st);
+    return check_launch("combine");
+}
+
+moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const void* X, const void* Wg,
+                          const void* W1, const void* W2, const void* dY, void* dX, void* dWg, float* dbg,
+                          void* dW1, void* dW2, void* workspace, size_t workspace_bytes, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    MOE_REQUIRE_PTR(X);
+    MOE_REQUIRE_PTR(Wg);
+    MOE_REQUIRE_PTR(W1);
+    MOE_REQUIRE_PTR(W2);
+    MOE_REQUIRE_PTR(dWg);
+    MOE_REQUIRE_PTR(dW1);
+    MOE_REQUIRE_PTR(dW2);
+    if (dbg && (reinterpret_cast<uintptr_t>(dbg) & 3u)) { set_error("dbg is not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    WsLayout L;
+    if ((s = check_ws(desc, workspace, workspace_bytes, &L)) != MOE_OK) return s;
+    const moe_desc_t& D = *desc;
+    if (D.N > 0) {
+        MOE_REQUIRE_PTR(dY);
+        MOE_REQUIRE_PTR(dX);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+
+    if (D.N > 0) {
+        launch_dcombine(D, dY, ws + L.Ys, plan->topk_w, plan->pos, ws + L.dYs, (float*)(ws + L.dl), st);
+        if ((s = check_launch("combine backward")) != MOE_OK) return s;
+    }
+
+    GemmArgs a{};
+    a.M = (long)D.N * D.k;
+    a.E = D.E;
+    a.counts = plan->counts;
+    a.offsets = plan->offsets;
+    a.tileP = (const int32_t*)(ws + L.tileP);
+    a.order = (const int32_t*)(ws + L.order);
+    a.out_f32 = D.grad_dtype == MOE_F32;
+    a.accumulate = D.accumulate;
+
+    if (D.N > 0) {
+        a.kind = kRowsNT_dGeLU;  // dZ = (dYs W2[e]^T) .* GeLU'(Z)
+        a.A = ws + L.dYs; a.B = W2; a.C = ws + L.dZ; a.Zin = ws + L.Z; a.K = D.d; a.Nout = D.h;
+        run_gemm(D, a, st);
+        if ((s = check_launch("expert layer 2 data gradient")) != MOE_OK) return s;
+    }
+    // The weight-gradient launches also run for N == 0: they write zeros (or leave the buffers when accumulating).
+    a.kind = kColsT;             // dW2[e] = H[seg]^T dYs[seg]
+    a.A = ws + L.H; a.B = ws + L.dYs; a.C = dW2; a.Zin = nullptr; a.K = D.h; a.Nout = D.d;
+    run_gemm(D, a, st);
+    if ((s = check_launch("expert layer 2 weight gradient")) != MOE_OK) return s;
+
+    if (D.N > 0) {
+        a.kind = kRowsNT;        // dXs = dZ W1[e]^T
+        a.A = ws + L.dZ; a.B = W1; a.C = ws + L.dXs; a.K = D.h; a.Nout = D.d;
+        run_gemm(D, a, st);
+        if ((s = check_launch("expert layer 1 data gradient")) != MOE_OK) return s;
+    }
+    a.kind = kColsT;             // dW1[e] = Xs[seg]^T dZ[seg]
+    a.A = ws + L.Xs; a.B = ws + L.dZ; a.C = dW1; a.K = D.d; a.Nout = D.h;
+    run_gemm(D, a, st);
+    if ((s = check_launch("expert layer 1 weight gradient")) != MOE_OK) return s;
+
+    launch_gate_bwd(D, L, ws + L.Xs, ws + L.dXs, Wg, (const float*)(ws + L.dl), plan->topk_idx, plan->pos,
+                    plan->perm, plan->counts, plan->offsets, dX, dWg, dbg, ws, st);
+    return check_launch("gate backward");
+}
+
+}  // extern "C"

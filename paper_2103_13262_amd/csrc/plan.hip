@@ -1,0 +1,164 @@
+// Counting, offsets and the stable position of every assignment inside its expert's segment
+// (Section 3.2: the samples per expert are counted first and the buffer offsets follow from
+// the counts; Section 4: the samples of one expert lie contiguously).  Integer work only.
+//
+//   plan_hist : per chunk of kPlanChunk assignments, an LDS histogram over experts.
+//   plan_scan : one workgroup; column scan over chunks -> counts and per-chunk bases, exclusive
+//               scan over experts -> offsets, tile prefix tables for four row-tile heights,
+//               experts ordered by descending count.
+//   plan_rank : per chunk, each wavefront ranks 64 assignments at a time with ballots (lanes
+//               that hold the same expert are found bit by bit), so rows keep assignment order.
+#include "common.h"
+
+namespace moe {
+
+__global__ __launch_bounds__(256) void plan_hist(const int32_t* __restrict__ idx, long M, int E,
+                                                 int32_t* __restrict__ hist)
+{
+    __shared__ int sh[kMaxE];
+    for (int e = threadIdx.x; e < E; e += 256) sh[e] = 0;
+    __syncthreads();
+    const long base = (long)blockIdx.x * kPlanChunk;
+    for (int q = 0; q < kPlanChunk / 256; ++q) {
+        const long a = base + q * 256 + threadIdx.x;
+        if (a < M) {
+            const int e = idx[a];
+            if (e >= 0 && e < E) atomicAdd(&sh[e], 1);
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 256) hist[(size_t)blockIdx.x * E + e] = sh[e];
+}
+
+// Exclusive scan of one int per thread over a 1024-thread workgroup. `total` receives the sum.
+__device__ __forceinline__ int block_excl_scan_1024(int v, int* s_wave /*[16]*/, int* total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += o;
+    }
+    __syncthreads();  // s_wave may still be read by a previous call
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    int wbase = 0, tot = 0;
+    for (int w = 0; w < 16; ++w) {
+        const int c = s_wave[w];
+        if (w < wave) wbase += c;
+        tot += c;
+    }
+    *total = tot;
+    return wbase + inc - v;
+}
+
+__global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ hist, int nb, int E, long M,
+                                                  int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+                                                  int32_t* __restrict__ tileP, int32_t* __restrict__ order)
+{
+    __shared__ int s_cnt[kMaxE];
+    __shared__ int s_wave[16];
+    const int e = threadIdx.x;
+    int cnt = 0;
+    if (e < E) {
+        for (int b = 0; b < nb; ++b) {
+            const int v = hist[(size_t)b * E + e];
+            hist[(size_t)b * E + e] = cnt;
+            cnt += v;
+        }
+        counts[e] = cnt;
+    }
+    s_cnt[e] = e < E ? cnt : -1;
+    int total;
+    const int off = block_excl_scan_1024(cnt, s_wave, &total);
+    if (e < E) offsets[e] = off;
+    if (e == 0) offsets[E] = total;
+    for (int q = 0; q < kNumTileHeights; ++q) {
+        const int bm = tile_height(q);
+        const int nt = e < E ? (cnt + bm - 1) / bm : 0;
+        const int p = block_excl_scan_1024(nt, s_wave, &total);
+        if (e < E) tileP[q * (E + 1) + e] = p;
+        if (e == 0) tileP[q * (E + 1) + E] = total;
+    }
+    __syncthreads();
+    if (e < E) {
+        int rank = 0;
+        for (int o = 0; o < E; ++o) {
+            const int c = s_cnt[o];
+            rank += (c > cnt || (c == cnt && o < e)) ? 1 : 0;
+        }
+        order[rank] = e;
+    }
+}
+
+__global__ __launch_bounds__(256) void plan_rank(const int32_t* __restrict__ idx, long M, int E, int nbits,
+                                                 const int32_t* __restrict__ base, const int32_t* __restrict__ offsets,
+                                                 int32_t* __restrict__ pos, int32_t* __restrict__ perm)
+{
+    __shared__ int wcnt[4][kMaxE];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int e = threadIdx.x; e < E; e += 256)
+        for (int w = 0; w < 4; ++w) wcnt[w][e] = 0;
+    __syncthreads();
+    const long cbase = (long)blockIdx.x * kPlanChunk + wave * 256;
+    int ev[4];
+    for (int s = 0; s < 4; ++s) {
+        const long a = cbase + s * 64 + lane;
+        int e = -1;
+        if (a < M) {
+            e = idx[a];
+            if (e < 0 || e >= E) e = -1;  // cannot happen for indices written by the gate kernel
+        }
+        ev[s] = e;
+        if (e >= 0) atomicAdd(&wcnt[wave][e], 1);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 256) {
+        int run = base[(size_t)blockIdx.x * E + e] + offsets[e];
+        for (int w = 0; w < 4; ++w) {
+            const int c = wcnt[w][e];
+            wcnt[w][e] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    for (int s = 0; s < 4; ++s) {
+        const int e = ev[s];
+        const bool valid = e >= 0;
+        unsigned long long mask = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = valid && ((e >> b) & 1);
+            const unsigned long long bal = __ballot(bit);
+            mask &= bit ? bal : ~bal;
+        }
+        int p = 0;
+        if (valid) {
+            const int rank = __popcll(mask & ((1ull << lane) - 1ull));
+            p = wcnt[wave][e] + rank;
+            const long a = cbase + s * 64 + lane;
+            pos[a] = p;
+            perm[p] = (int32_t)a;
+        }
+        __syncthreads();  // every lane has read its counter before the group leader advances it
+        if (valid && (mask >> lane) == 1ull) wcnt[wave][e] = p + 1;
+        __syncthreads();
+    }
+}
+
+void launch_plan(const moe_desc_t& D, const WsLayout& L, const int32_t* topk_idx, int32_t* counts,
+                 int32_t* offsets, int32_t* pos, int32_t* perm, char* ws, hipStream_t st)
+{
+    const long M = (long)D.N * D.k;
+    int32_t* hist = (int32_t*)(ws + L.hist);
+    int32_t* tileP = (int32_t*)(ws + L.tileP);
+    int32_t* order = (int32_t*)(ws + L.order);
+    int nbits = 0;
+    while ((1 << nbits) < D.E) ++nbits;
+    if (L.nb > 0) hipLaunchKernelGGL(plan_hist, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, hist);
+    hipLaunchKernelGGL(plan_scan, dim3(1), dim3(1024), 0, st, hist, L.nb, D.E, M, counts, offsets, tileP, order);
+    if (L.nb > 0)
+        hipLaunchKernelGGL(plan_rank, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, nbits, (const int32_t*)hist,
+                           (const int32_t*)offsets, pos, perm);
+}
+
+}  // namespace moe

@@ -1,0 +1,299 @@
+// Row-movement kernels around the expert matrix products (Section 4: "scatter" puts the
+// samples of one expert into contiguous memory, "gather" puts the rows back in their original
+// order; Algorithm 1: y accumulates score_i * E_i(x)), and their gradients.  All are bound by
+// HBM traffic: every thread moves 16-byte pieces of a row, rows are addressed through pos/perm.
+#include "common.h"
+
+namespace moe {
+
+// 16 bytes of a row as floats: 8 bf16 or 4 fp32 elements.
+template <typename T> struct Vec;
+template <> struct Vec<unsigned short> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void load(const void* base, size_t chunk, float* f)
+    {
+        const uint4 v = ((const uint4*)base)[chunk];
+        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(void* base, size_t chunk, const float* f)
+    {
+        unsigned w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (unsigned)f32_to_bf16(f[2 * i]) | ((unsigned)f32_to_bf16(f[2 * i + 1]) << 16);
+        ((uint4*)base)[chunk] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void load(const void* base, size_t chunk, float* f)
+    {
+        const float4 v = ((const float4*)base)[chunk];
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    static __device__ __forceinline__ void store(void* base, size_t chunk, const float* f)
+    {
+        ((float4*)base)[chunk] = make_float4(f[0], f[1], f[2], f[3]);
+    }
+};
+
+// ---- scatter: Xs[r,:] = X[perm[r] / k, :] ------------------------------------------------------
+__global__ __launch_bounds__(256) void scatter_rows(const uint4* __restrict__ X, const int32_t* __restrict__ perm,
+                                                    uint4* __restrict__ Xs, long M, int k, int cpr)
+{
+    const long total = M * cpr;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const long r = i / cpr;
+        const int c = (int)(i - r * cpr);
+        const long t = perm[r] / k;
+        Xs[i] = X[t * cpr + c];
+    }
+}
+
+// ---- combine: Y[t,:] = sum_j w[t,j] * Ys[pos[t*k+j], :]  (slots in ascending j, fp32) ---------
+template <typename T>
+__global__ __launch_bounds__(256) void combine_rows(const void* __restrict__ Ys, const float* __restrict__ topk_w,
+                                                    const int32_t* __restrict__ pos, void* __restrict__ Y, long N,
+                                                    int k, int cpr)
+{
+    constexpr int V = Vec<T>::N;
+    const long total = N * cpr;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const long t = i / cpr;
+        const int c = (int)(i - t * cpr);
+        float acc[V];
+#pragma unroll
+        for (int u = 0; u < V; ++u) acc[u] = 0.f;
+        for (int j = 0; j < k; ++j) {
+            const long a = t * k + j;
+            const float w = topk_w[a];
+            float v[V];
+            Vec<T>::load(Ys, (size_t)pos[a] * cpr + c, v);
+#pragma unroll
+            for (int u = 0; u < V; ++u) acc[u] = fmaf(w, v[u], acc[u]);
+        }
+        Vec<T>::store(Y, (size_t)i, acc);
+    }
+}
+
+// ---- combine backward: one wavefront per token -------------------------------------------------
+//   dYs[pos[a],:] = w[a] * dY[t,:];  dw[a] = <dY[t,:], Ys[pos[a],:]>;  dl_j = w_j (dw_j - sum_i w_i dw_i)
+template <typename T>
+__global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY, const void* __restrict__ Ys,
+                                                     const float* __restrict__ topk_w,
+                                                     const int32_t* __restrict__ pos, void* __restrict__ dYs,
+                                                     float* __restrict__ dl, long N, int k, int cpr)
+{
+    constexpr int V = Vec<T>::N;
+    const int lane = threadIdx.x & 63;
+    const long t = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= N) return;
+    float w[kMaxK], dw[kMaxK];
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j) {
+        if (j >= k) break;
+        const long a = t * k + j;
+        const size_t r = (size_t)pos[a];
+        w[j] = topk_w[a];
+        float part = 0.f;
+        for (int c = lane; c < cpr; c += 64) {
+            float g[V], y[V], o[V];
+            Vec<T>::load(dY, (size_t)t * cpr + c, g);
+            Vec<T>::load(Ys, r * cpr + c, y);
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                o[u] = w[j] * g[u];
+                part = fmaf(g[u], y[u], part);
+            }
+            Vec<T>::store(dYs, r * cpr + c, o);
+        }
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+        dw[j] = part;
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j)
+        if (j < k) s = fmaf(w[j], dw[j], s);
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < kMaxK; ++j)
+            if (j < k) dl[t * k + j] = w[j] * (dw[j] - s);
+    }
+}
+
+// ---- dX[t,:] = sum_j dXs[pos[a],:] + sum_j dl[a] * Wg[:, idx[a]] ------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs, const T* __restrict__ Wg,
+                                                   const float* __restrict__ dl, const int32_t* __restrict__ topk_idx,
+                                                   const int32_t* __restrict__ pos, void* __restrict__ dX, long N, int k,
+                                                   int E, int cpr)
+{
+    constexpr int V = Vec<T>::N;
+    const long total = N * cpr;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const long t = i / cpr;
+        const int c = (int)(i - t * cpr);
+        float acc[V];
+#pragma unroll
+        for (int u = 0; u < V; ++u) acc[u] = 0.f;
+        for (int j = 0; j < k; ++j) {
+            float v[V];
+            Vec<T>::load(dXs, (size_t)pos[t * k + j] * cpr + c, v);
+#pragma unroll
+            for (int u = 0; u < V; ++u) acc[u] += v[u];
+        }
+        for (int j = 0; j < k; ++j) {
+            const long a = t * k + j;
+            const float g = dl[a];
+            const int e = topk_idx[a];
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                const T wv = Wg[(size_t)(c * V + u) * E + e];
+                float wf;
+                if constexpr (sizeof(T) == 2) wf = bf16_to_f32(wv); else wf = wv;
+                acc[u] = fmaf(g, wf, acc[u]);
+            }
+        }
+        Vec<T>::store(dX, (size_t)i, acc);
+    }
+}
+
+// ---- dWg[:,e] = sum over rows r of segment e of dl[perm[r]] * Xs[r,:]  (fixed order) ----------
+// grid (E, S, ceil(cpr/128)); each thread owns one 16-byte column piece and walks its share of rows.
+template <typename T>
+__global__ __launch_bounds__(128) void dwg_partial(const void* __restrict__ Xs, const float* __restrict__ dl,
+                                                   const int32_t* __restrict__ perm, const int32_t* __restrict__ counts,
+                                                   const int32_t* __restrict__ offsets, float* __restrict__ part,
+                                                   float* __restrict__ bpart, int S, int d, int cpr)
+{
+    constexpr int V = Vec<T>::N;
+    const int e = blockIdx.x, s = blockIdx.y;
+    const int c = blockIdx.z * 128 + threadIdx.x;
+    const int cnt = counts[e], off = offsets[e];
+    const int per = (cnt + S - 1) / S;
+    int lo = s * per;
+    int hi = lo + per < cnt ? lo + per : cnt;
+    if (lo > hi) lo = hi;
+    float acc[V], sdl = 0.f;
+#pragma unroll
+    for (int u = 0; u < V; ++u) acc[u] = 0.f;
+    if (c < cpr) {
+        for (int r = off + lo; r < off + hi; ++r) {
+            const float g = dl[perm[r]];
+            float v[V];
+            Vec<T>::load(Xs, (size_t)r * cpr + c, v);
+#pragma unroll
+            for (int u = 0; u < V; ++u) acc[u] = fmaf(g, v[u], acc[u]);
+            sdl += g;
+        }
+        float* dst = part + ((size_t)e * S + s) * d + (size_t)c * V;
+#pragma unroll
+        for (int u = 0; u < V; ++u) dst[u] = acc[u];
+        if (c == 0) bpart[(size_t)e * S + s] = sdl;
+    }
+}
+
+template <typename G>
+__global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part, const float* __restrict__ bpart,
+                                                 G* __restrict__ dWg, float* __restrict__ dbg, int S, int d, int E,
+                                                 int accumulate)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;  // i = row * E + e of dWg
+    if (i < (long)d * E) {
+        const int row = (int)(i / E), e = (int)(i % E);
+        float s = 0.f;
+        for (int q = 0; q < S; ++q) s += part[((size_t)e * S + q) * d + row];
+        if constexpr (sizeof(G) == 2) {
+            if (accumulate) s += bf16_to_f32(dWg[i]);
+            dWg[i] = f32_to_bf16(s);
+        } else {
+            if (accumulate) s += dWg[i];
+            dWg[i] = s;
+        }
+    }
+    if (dbg && i < E) {
+        float s = 0.f;
+        for (int q = 0; q < S; ++q) s += bpart[(size_t)i * S + q];
+        if (accumulate) s += dbg[i];
+        dbg[i] = s;
+    }
+}
+
+// ---- launchers -----------------------------------------------------------------------------------
+static unsigned grid_for(long items)
+{
+    long g = (items + 255) / 256;
+    if (g < 1) g = 1;
+    if (g > 256 * 32) g = 256 * 32;
+    return (unsigned)g;
+}
+
+void launch_scatter(const moe_desc_t& D, const void* X, const int32_t* perm, void* Xs, hipStream_t st)
+{
+    const long M = (long)D.N * D.k;
+    const int cpr = (int)((size_t)D.d * dtype_size(D.dtype) / 16);
+    hipLaunchKernelGGL(scatter_rows, dim3(grid_for(M * cpr)), dim3(256), 0, st, (const uint4*)X, perm, (uint4*)Xs, M,
+                       D.k, cpr);
+}
+
+void launch_combine(const moe_desc_t& D, const void* Ys, const float* topk_w, const int32_t* pos, void* Y,
+                    hipStream_t st)
+{
+    const int cpr = (int)((size_t)D.d * dtype_size(D.dtype) / 16);
+    const unsigned g = grid_for((long)D.N * cpr);
+    if (D.dtype == MOE_BF16)
+        hipLaunchKernelGGL(combine_rows<unsigned short>, dim3(g), dim3(256), 0, st, Ys, topk_w, pos, Y, (long)D.N, D.k, cpr);
+    else
+        hipLaunchKernelGGL(combine_rows<float>, dim3(g), dim3(256), 0, st, Ys, topk_w, pos, Y, (long)D.N, D.k, cpr);
+}
+
+void launch_dcombine(const moe_desc_t& D, const void* dY, const void* Ys, const float* topk_w,
+                     const int32_t* pos, void* dYs, float* dl, hipStream_t st)
+{
+    const int cpr = (int)((size_t)D.d * dtype_size(D.dtype) / 16);
+    const unsigned g = (unsigned)((D.N + 3) / 4);
+    if (D.dtype == MOE_BF16)
+        hipLaunchKernelGGL(dcombine_rows<unsigned short>, dim3(g), dim3(256), 0, st, dY, Ys, topk_w, pos, dYs, dl,
+                           (long)D.N, D.k, cpr);
+    else
+        hipLaunchKernelGGL(dcombine_rows<float>, dim3(g), dim3(256), 0, st, dY, Ys, topk_w, pos, dYs, dl, (long)D.N,
+                           D.k, cpr);
+}
+
+void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, const void* dXs, const void* Wg,
+                     const float* dl, const int32_t* topk_idx, const int32_t* pos, const int32_t* perm,
+                     const int32_t* counts, const int32_t* offsets, void* dX, void* dWg, float* dbg, char* ws,
+                     hipStream_t st)
+{
+    const int cpr = (int)((size_t)D.d * dtype_size(D.dtype) / 16);
+    float* part = (float*)(ws + L.dwg_part);
+    float* bpart = (float*)(ws + L.dbg_part);
+    const dim3 pg(D.E, L.S, (cpr + 127) / 128);
+    const unsigned fg = (unsigned)(((long)D.d * D.E + 255) / 256);
+    const unsigned xg = grid_for((long)D.N * cpr);
+    if (D.dtype == MOE_BF16) {
+        using T = unsigned short;
+        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, part, bpart, L.S, D.d, cpr);
+        if (D.grad_dtype == MOE_BF16)
+            hipLaunchKernelGGL(dwg_final<unsigned short>, dim3(fg), dim3(256), 0, st, (const float*)part,
+                               (const float*)bpart, (unsigned short*)dWg, dbg, L.S, D.d, D.E, D.accumulate);
+        else
+            hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
+                               (float*)dWg, dbg, L.S, D.d, D.E, D.accumulate);
+        hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const T*)Wg, dl, topk_idx, pos, dX,
+                           (long)D.N, D.k, D.E, cpr);
+    } else {
+        using T = float;
+        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, part, bpart, L.S, D.d, cpr);
+        hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
+                           (float*)dWg, dbg, L.S, D.d, D.E, D.accumulate);
+        hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const T*)Wg, dl, topk_idx, pos, dX,
+                           (long)D.N, D.k, D.E, cpr);
+    }
+}
+
+}  // namespace moe

@@ -1,0 +1,131 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C ABI, run the
+oracle on the same bits, and the error metric.  (The two sides share only the inputs.)"""
+import numpy as np
+
+from paper_2103_13262_amd import binding as B
+from paper_2103_13262_amd.synth import Workload, make_inputs
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # max relative error stated for fp32 / bf16 outputs and gradients
+
+
+def rel_err(got, ref):
+    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref)): elementwise relative error with the
+    tensor's RMS as floor, so elements that are tiny by cancellation do not dominate."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms == 0.0:
+        return 0.0 if not np.any(got) else float("inf")
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rms)))
+
+
+def to_torch(a, dtype_name, device):
+    import torch
+
+    if dtype_name == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def to_numpy64(t):
+    import torch
+
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+class GpuRun:
+    """One problem on the GPU: plan, forward, backward through the C ABI."""
+
+    def __init__(self, w: Workload, inputs, grad_dtype=None, accumulate=0, device="cuda:0"):
+        import torch
+
+        self.torch, self.w, self.device = torch, w, device
+        dt = B.MOE_BF16 if w.dtype == "bf16" else B.MOE_F32
+        gd = dt if grad_dtype is None else grad_dtype
+        self.desc = B.make_desc(w.N, w.d, w.h, w.E, w.k, dt, gd, accumulate)
+        self.buf = B.MoeLayerBuffers(self.desc, device)
+        tt = lambda n: to_torch(inputs[n], w.dtype, device)
+        self.X, self.Wg, self.W1, self.W2 = tt("X"), tt("Wg"), tt("W1"), tt("W2")
+        self.dY = tt("dY") if "dY" in inputs else None
+        self.bg = None if inputs.get("bg") is None else torch.from_numpy(inputs["bg"]).to(device)
+        act = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        grd = torch.bfloat16 if gd == B.MOE_BF16 else torch.float32
+        # outputs are poisoned so that an element the kernels skip shows up as a mismatch
+        self.Y = torch.full((max(w.N, 1), w.d), float("nan"), dtype=act, device=device)
+        self.dX = torch.full((max(w.N, 1), w.d), float("nan"), dtype=act, device=device)
+        self.dWg = torch.full((w.d, w.E), float("nan"), dtype=grd, device=device)
+        self.dbg = torch.full((max(w.E, 4),), float("nan"), dtype=torch.float32, device=device)
+        self.dW1 = torch.full((w.E, w.d, w.h), float("nan"), dtype=grd, device=device)
+        self.dW2 = torch.full((w.E, w.h, w.d), float("nan"), dtype=grd, device=device)
+
+    def plan(self):
+        b = self.buf
+        B.moe_plan(self.desc, self.X, self.Wg, self.bg, b.plan, b.workspace, b.ws_bytes, b.stream())
+
+    def forward(self):
+        b = self.buf
+        B.moe_forward(self.desc, b.plan, self.X, self.W1, self.W2, None, None, self.Y, b.workspace, b.ws_bytes,
+                      b.stream())
+
+    def backward(self):
+        b = self.buf
+        B.moe_backward(self.desc, b.plan, self.X, self.Wg, self.W1, self.W2, self.dY, self.dX, self.dWg, self.dbg,
+                       self.dW1, self.dW2, b.workspace, b.ws_bytes, b.stream())
+
+    def run(self, backward=True):
+        self.plan()
+        self.forward()
+        if backward:
+            self.backward()
+        self.torch.cuda.synchronize()
+        return self
+
+    # ---- results as numpy ----
+    def plan_arrays(self):
+        b, w = self.buf, self.w
+        M = w.N * w.k
+        g = lambda t, n: t.cpu().numpy()[:n]
+        return dict(idx=b.topk_idx.cpu().numpy(), w=b.topk_w.cpu().numpy(), counts=g(b.counts, w.E),
+                    offsets=g(b.offsets, w.E + 1), pos=g(b.pos, M), perm=g(b.perm, M))
+
+    def region(self, name):
+        """A named workspace intermediate as float64 numpy [rows, width]."""
+        torch, w = self.torch, self.w
+        off, n = B.moe_workspace_region(self.desc, name)
+        raw = self.buf.workspace[off:off + n]
+        if name == "dl":
+            return to_numpy64(raw.view(torch.float32))
+        width = w.h if name in ("Z", "H", "dZ") else w.d
+        t = raw.view(torch.bfloat16 if w.dtype == "bf16" else torch.float32)
+        return to_numpy64(t.view(-1, width))
+
+
+def oracle_problem(w: Workload, inputs, dY=True):
+    import oracle as orc
+
+    bg = None if inputs.get("bg") is None else inputs["bg"].astype(np.float64)
+    return orc.OracleProblem(inputs["X"], inputs["Wg"], inputs["W1"], inputs["W2"], w.k, bg=bg,
+                             dY=inputs["dY"] if dY and "dY" in inputs else None)
+
+
+def check_plan_exact(run: GpuRun, inputs):
+    """Indices, counts, offsets and the permutation must equal the oracle's bit for bit."""
+    import oracle as orc
+
+    w = run.w
+    p = oracle_problem(w, inputs, dY=False)
+    idx, wt, _ = orc.gate(p)
+    counts, offsets, pos, perm = orc.plan(idx, w.E)
+    got = run.plan_arrays()
+    np.testing.assert_array_equal(got["idx"], idx)
+    np.testing.assert_array_equal(got["counts"], counts)
+    np.testing.assert_array_equal(got["offsets"], offsets)
+    np.testing.assert_array_equal(got["pos"], pos)
+    np.testing.assert_array_equal(got["perm"], perm)
+    np.testing.assert_allclose(got["w"], wt, rtol=0, atol=1e-6)
+    if w.k == 1:
+        assert np.all(got["w"] == 1.0)
+    return dict(idx=idx, w=wt, counts=counts, offsets=offsets, pos=pos, perm=perm)
