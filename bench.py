@@ -1,0 +1,145 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE layer hot path on one MI355X.
+
+A step is one pass of the whole path -- moe_plan + moe_forward + moe_backward -- over one batch
+of synthetic input that is already resident in HBM.  Protocol as in the paper's Section 5.1:
+warm-up rounds that are not counted, then the timed runs (16 by default), mean time.
+
+Prints ONE JSON line: whole-step throughput in tokens/s (`value`), the roofline of the dominant
+kernel (the grouped matrix product, timed per launch with HIP events on the launch stream in a
+second pass of the same number of steps) and the CPU oracle timed on a bounded token sample.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+METRIC = "MoE layer fwd+bwd tokens/sec and grouped-GEMM % of bf16 MFMA peak, 1 GPU"
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3      # vector fp32 (the fp32 workload does not use the matrix cores)
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C1", help="C0..C4 (C1 is the configuration the metric is quoted on)")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=-1, help="tokens of the oracle sample (0: skip)")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, inputs, n_tokens):
+    """The fp64 oracle, as it stands, on a seeded token sample of the same workload."""
+    import oracle as orc
+    from oracle.build import build_oracle
+
+    build_oracle(force=False)
+    bg = inputs["bg"].astype(np.float64)
+    p = orc.OracleProblem(inputs["X"], inputs["Wg"], inputs["W1"], inputs["W2"], w.k, bg=bg, dY=inputs["dY"])
+    toks = np.sort(np.random.default_rng(w.seed).choice(w.N, size=min(n_tokens, w.N), replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    orc.layer(p, tokens=toks)
+    dt = time.perf_counter() - t0
+    return {"value": toks.size / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{toks.size} of {w.N} tokens of {w.name} (seeded subset), full forward+backward incl. all "
+                      f"weight gradients, {dt:.1f} s"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (all experts local, no collectives); --gpus {a.gpus} is not "
+              "supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2103_13262_amd import binding as B
+    from paper_2103_13262_amd.synth import WORKLOADS, make_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()   # raises if the HIP library has not been built: there is no fallback
+    w = WORKLOADS[a.workload]
+    inputs = make_inputs(w)
+    dev = torch.device("cuda:0")
+    bf = w.dtype == "bf16"
+    dt = B.MOE_BF16 if bf else B.MOE_F32
+
+    def up(x):
+        if bf:
+            return torch.from_numpy(x.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(x).to(dev)
+
+    X, Wg, W1, W2, dY = (up(inputs[n]) for n in ("X", "Wg", "W1", "W2", "dY"))
+    bg = torch.from_numpy(inputs["bg"]).to(dev)
+    desc = B.make_desc(w.N, w.d, w.h, w.E, w.k, dt, dt, 0)
+    buf = B.MoeLayerBuffers(desc, dev)
+    act = torch.bfloat16 if bf else torch.float32
+    Y, dX = torch.empty_like(X), torch.empty_like(X)
+    dWg, dW1, dW2 = torch.empty_like(Wg), torch.empty_like(W1), torch.empty_like(W2)
+    dbg = torch.empty(max(w.E, 4), dtype=torch.float32, device=dev)
+    stream = buf.stream()
+
+    def step():
+        B.moe_plan(desc, X, Wg, bg, buf.plan, buf.workspace, buf.ws_bytes, stream)
+        B.moe_forward(desc, buf.plan, X, W1, W2, None, None, Y, buf.workspace, buf.ws_bytes, stream)
+        B.moe_backward(desc, buf.plan, X, Wg, W1, W2, dY, dX, dWg, dbg, dW1, dW2, buf.workspace, buf.ws_bytes, stream)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / a.steps
+
+    # second pass of the same steps with per-kernel HIP events (recorded on the launch stream)
+    B.moe_profile_enable(True)
+    for _ in range(a.steps):
+        step()
+    prof = B.moe_profile_read()
+    B.moe_profile_enable(False)
+
+    flops_launch = 2.0 * w.M * w.d * w.h                     # one grouped product: 2 M d h
+    kern = {n: {"launches_per_step": c / a.steps, "avg_us": 1e3 * t / c} for n, (c, t) in prof.items()}
+    gemm = {n: v for n, v in prof.items() if n.startswith("ggemm_")}
+    g_launches = sum(c for c, _ in gemm.values())
+    g_ms = sum(t for _, t in gemm.values())
+    avg_launch_ms = g_ms / g_launches
+    achieved = flops_launch / (avg_launch_ms * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if bf else PEAK_FP32_TFLOPS
+    for n, (c, t) in gemm.items():
+        kern[n]["tflops"] = flops_launch / (t / c * 1e-3) / 1e12
+    roofline = {"bound": "mfma" if bf else "alu", "kernel": "ggemm_bf16_kernel (6 launches per step)" if bf
+                else "ggemm_f32_kernel (6 launches per step)",
+                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "flops_per_launch": flops_launch, "avg_launch_us": avg_launch_ms * 1e3}
+
+    out = {
+        "metric": METRIC, "value": w.N / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: N={w.N} d_m={w.d} d_h={w.h} E={w.E} top-{w.k} {w.dtype}, "
+                               f"{'Zipf s=%g gate bias' % w.zipf_s if w.zipf_s else 'near-uniform gate'}; "
+                               "step = moe_plan + moe_forward + moe_backward"},
+        "expert_gemm_tflops_whole_step": w.expert_flops() / (ms_step * 1e-3) / 1e12,
+        "grouped_gemm_pct_of_bf16_mfma_peak": 100.0 * achieved / PEAK_BF16_TFLOPS if bf else None,
+        "roofline": roofline,
+        "kernels": kern,
+    }
+    n_cpu = a.cpu_sample_tokens
+    if n_cpu < 0:   # about 10-30 s of CPU work: the oracle costs ~24 M d h flop-pairs per assignment
+        n_cpu = int(max(8, min(w.N, 2.5e11 / (12.0 * w.k * w.d * w.h))))
+    if n_cpu > 0:
+        out["cpu_baseline"] = cpu_baseline(w, inputs, n_cpu)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

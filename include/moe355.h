@@ -130,6 +130,25 @@ moe_status_t moe_backward(const moe_desc_t *desc, const moe_plan_t *plan, const 
  */
 moe_status_t moe_workspace_region(const moe_desc_t *desc, const char *name, size_t *offset, size_t *bytes);
 
+/*
+ * Diagnostics: per-kernel timing with HIP events, off by default.  While enabled, every kernel
+ * group the three calls launch is bracketed by two events recorded on the caller's stream (this
+ * creates events, the one place where the library allocates, and adds a few microseconds per
+ * launch, so whole-step timings should be taken with it disabled).
+ *   moe_profile_enable(on)  switches it on (1) or off (0); switching discards pending records.
+ *   moe_profile_read(out, max)  WAITS for the recorded events (the only call that synchronises
+ *     with the device), writes up to `max` entries -- one per kernel group, with the number of
+ *     launches and their summed duration since the last read -- and returns how many it wrote
+ *     (negative status on a HIP error).  `name` points to static storage.
+ */
+typedef struct {
+    const char *name; /* e.g. "ggemm_fc1_gelu", "scatter"                                        */
+    int32_t launches; /* launches recorded since the last read                                  */
+    double total_ms;  /* summed device time of those launches                                   */
+} moe_kernel_time_t;
+moe_status_t moe_profile_enable(int on);
+int moe_profile_read(moe_kernel_time_t *out, int max_entries);
+
 /* Text of the last error on this thread ("" if none). Static storage; do not free. */
 const char *moe_last_error(void);
 

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe355.so")
 MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP = 0, -1, -2, -3, -4
 MOE_F32, MOE_BF16 = 0, 1
 EXPORTS = ("moe_workspace_bytes", "moe_workspace_region", "moe_plan", "moe_forward", "moe_backward",
-           "moe_last_error")
+           "moe_last_error", "moe_profile_enable", "moe_profile_read")
 
 
 class MoeDesc(C.Structure):
@@ -25,6 +25,10 @@ class MoeDesc(C.Structure):
 class MoePlan(C.Structure):
     _fields_ = [("topk_idx", C.c_void_p), ("topk_w", C.c_void_p), ("counts", C.c_void_p),
                 ("offsets", C.c_void_p), ("pos", C.c_void_p), ("perm", C.c_void_p)]
+
+
+class MoeKernelTime(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("launches", C.c_int32), ("total_ms", C.c_double)]
 
 
 class MoeError(RuntimeError):
@@ -44,6 +48,10 @@ def lib():
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2103_13262_amd.build` "
                 "(there is no fallback path)")
+        # torch first: its bundled HIP runtime must be the one this process initialises, so that the
+        # library's kernels run on the same runtime (and devices, streams) as torch's allocations.
+        import torch  # noqa: F401
+
         L = C.CDLL(LIB_PATH)
         L.moe_workspace_bytes.restype = C.c_size_t
         L.moe_workspace_bytes.argtypes = [C.POINTER(MoeDesc)]
@@ -59,6 +67,10 @@ def lib():
         L.moe_workspace_region.restype = C.c_int
         L.moe_workspace_region.argtypes = [C.POINTER(MoeDesc), C.c_char_p, C.POINTER(C.c_size_t),
                                            C.POINTER(C.c_size_t)]
+        L.moe_profile_enable.restype = C.c_int
+        L.moe_profile_enable.argtypes = [C.c_int]
+        L.moe_profile_read.restype = C.c_int
+        L.moe_profile_read.argtypes = [C.POINTER(MoeKernelTime), C.c_int]
         _lib = L
     return _lib
 
@@ -90,6 +102,19 @@ def moe_workspace_region(desc, name):
     off, n = C.c_size_t(0), C.c_size_t(0)
     _check(lib().moe_workspace_region(C.byref(desc), name.encode(), C.byref(off), C.byref(n)))
     return int(off.value), int(n.value)
+
+
+def moe_profile_enable(on):
+    _check(lib().moe_profile_enable(1 if on else 0))
+
+
+def moe_profile_read():
+    """{kernel group: (launches, total_ms)} since the last read; waits for the recorded work."""
+    buf = (MoeKernelTime * 32)()
+    n = lib().moe_profile_read(buf, 32)
+    if n < 0:
+        _check(n)
+    return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(n)}
 
 
 def moe_last_error():

@@ -5,6 +5,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "common.h"
 
@@ -29,6 +31,43 @@ moe_status_t check_launch(const char* what)
     }
     return MOE_OK;
 }
+
+// ---- optional per-kernel timing (diagnostics) --------------------------------------------------
+enum Slot { S_GATE, S_PLAN, S_SCATTER, S_FC1, S_FC2, S_COMBINE, S_DCOMBINE, S_DH, S_DW2, S_DXS, S_DW1, S_GATEBWD, S_COUNT };
+static const char* const kSlotNames[S_COUNT] = {"gate_topk", "plan", "scatter", "ggemm_fc1_gelu", "ggemm_fc2",
+                                                "combine", "dcombine", "ggemm_dh_dgelu", "ggemm_dw2", "ggemm_dxs",
+                                                "ggemm_dw1", "gate_bwd"};
+struct TimedRecord { int slot; hipEvent_t a, b; };
+static std::mutex g_prof_mu;
+static bool g_prof_on = false;
+static std::vector<TimedRecord> g_prof_pending;
+static std::vector<hipEvent_t> g_prof_pool;
+
+static hipEvent_t prof_event()
+{
+    if (!g_prof_pool.empty()) { hipEvent_t e = g_prof_pool.back(); g_prof_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Brackets the kernels enqueued during its lifetime with two events when profiling is on.
+struct ScopedTimer {
+    hipStream_t st; TimedRecord r{}; bool on = false;
+    ScopedTimer(int slot, hipStream_t s) : st(s)
+    {
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        if (!g_prof_on) return;
+        r.slot = slot; r.a = prof_event(); r.b = prof_event();
+        on = r.a && r.b && hipEventRecord(r.a, st) == hipSuccess;
+    }
+    ~ScopedTimer()
+    {
+        if (!on) return;
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        if (hipEventRecord(r.b, st) == hipSuccess) g_prof_pending.push_back(r);
+    }
+};
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -107,6 +146,42 @@ size_t moe_workspace_bytes(const moe_desc_t* desc)
 
 const char* moe_last_error(void) { return g_err; }
 
+moe_status_t moe_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (auto& r : g_prof_pending) { g_prof_pool.push_back(r.a); g_prof_pool.push_back(r.b); }
+    g_prof_pending.clear();
+    g_prof_on = on != 0;
+    return MOE_OK;
+}
+
+int moe_profile_read(moe_kernel_time_t* out, int max_entries)
+{
+    g_err[0] = 0;
+    if (!out || max_entries < 0) { set_error("out is NULL or max_entries < 0"); return MOE_ERR_INVALID_ARG; }
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    int launches[S_COUNT] = {};
+    double ms[S_COUNT] = {};
+    int rc = 0;
+    for (auto& r : g_prof_pending) {
+        float t = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) {
+            set_error("profile: %s", hipGetErrorString(hipGetLastError()));
+            rc = MOE_ERR_HIP;
+        }
+        launches[r.slot] += 1;
+        ms[r.slot] += t;
+        g_prof_pool.push_back(r.a);
+        g_prof_pool.push_back(r.b);
+    }
+    g_prof_pending.clear();
+    if (rc) return rc;
+    int n = 0;
+    for (int s = 0; s < S_COUNT && n < max_entries; ++s)
+        if (launches[s]) out[n++] = moe_kernel_time_t{kSlotNames[s], launches[s], ms[s]};
+    return n;
+}
+
 moe_status_t moe_workspace_region(const moe_desc_t* desc, const char* name, size_t* offset, size_t* bytes)
 {
     g_err[0] = 0;
@@ -141,11 +216,15 @@ moe_status_t moe_plan(const moe_desc_t* desc, const void* X, const void* Wg, con
     hipStream_t st = (hipStream_t)stream;
     const moe_desc_t& D = *desc;
     if (D.N > 0) {
+        ScopedTimer tm(S_GATE, st);
         launch_gate_topk(D, X, Wg, bg, plan->topk_idx, plan->topk_w, st);
         if ((s = check_launch("gate/top-k")) != MOE_OK) return s;
     }
     // With N == 0 the plan kernels still run: they write counts = 0, offsets = 0 and empty tile tables.
-    launch_plan(D, L, plan->topk_idx, plan->counts, plan->offsets, plan->pos, plan->perm, (char*)workspace, st);
+    {
+        ScopedTimer tm(S_PLAN, st);
+        launch_plan(D, L, plan->topk_idx, plan->counts, plan->offsets, plan->pos, plan->perm, (char*)workspace, st);
+    }
     return check_launch("plan");
 }
 
@@ -169,7 +248,7 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     hipStream_t st = (hipStream_t)stream;
     char* ws = (char*)workspace;
 
-    launch_scatter(D, X, plan->perm, ws + L.Xs, st);
+    { ScopedTimer tm(S_SCATTER, st); launch_scatter(D, X, plan->perm, ws + L.Xs, st); }
     if ((s = check_launch("scatter")) != MOE_OK) return s;
 
     GemmArgs a{};
@@ -182,15 +261,15 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
     a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h;
-    run_gemm(D, a, st);
+    { ScopedTimer tm(S_FC1, st); run_gemm(D, a, st); }
     if ((s = check_launch("expert layer 1")) != MOE_OK) return s;
 
     a.kind = kRowsNN;       // Ys = H W2[e]
     a.A = ws + L.H; a.B = W2; a.C = ws + L.Ys; a.C2 = nullptr; a.K = D.h; a.Nout = D.d;
-    run_gemm(D, a, st);
+    { ScopedTimer tm(S_FC2, st); run_gemm(D, a, st); }
     if ((s = check_launch("expert layer 2")) != MOE_OK) return s;
 
-    launch_combine(D, ws + L.Ys, plan->topk_w, plan->pos, Y, st);
+    { ScopedTimer tm(S_COMBINE, st); launch_combine(D, ws + L.Ys, plan->topk_w, plan->pos, Y, st); }
     return check_launch("combine");
 }
 
@@ -221,6 +300,7 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     char* ws = (char*)workspace;
 
     if (D.N > 0) {
+        ScopedTimer tm(S_DCOMBINE, st);
         launch_dcombine(D, dY, ws + L.Ys, plan->topk_w, plan->pos, ws + L.dYs, (float*)(ws + L.dl), st);
         if ((s = check_launch("combine backward")) != MOE_OK) return s;
     }
@@ -238,28 +318,31 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     if (D.N > 0) {
         a.kind = kRowsNT_dGeLU;  // dZ = (dYs W2[e]^T) .* GeLU'(Z)
         a.A = ws + L.dYs; a.B = W2; a.C = ws + L.dZ; a.Zin = ws + L.Z; a.K = D.d; a.Nout = D.h;
-        run_gemm(D, a, st);
+        { ScopedTimer tm(S_DH, st); run_gemm(D, a, st); }
         if ((s = check_launch("expert layer 2 data gradient")) != MOE_OK) return s;
     }
     // The weight-gradient launches also run for N == 0: they write zeros (or leave the buffers when accumulating).
     a.kind = kColsT;             // dW2[e] = H[seg]^T dYs[seg]
     a.A = ws + L.H; a.B = ws + L.dYs; a.C = dW2; a.Zin = nullptr; a.K = D.h; a.Nout = D.d;
-    run_gemm(D, a, st);
+    { ScopedTimer tm(S_DW2, st); run_gemm(D, a, st); }
     if ((s = check_launch("expert layer 2 weight gradient")) != MOE_OK) return s;
 
     if (D.N > 0) {
         a.kind = kRowsNT;        // dXs = dZ W1[e]^T
         a.A = ws + L.dZ; a.B = W1; a.C = ws + L.dXs; a.K = D.h; a.Nout = D.d;
-        run_gemm(D, a, st);
+        { ScopedTimer tm(S_DXS, st); run_gemm(D, a, st); }
         if ((s = check_launch("expert layer 1 data gradient")) != MOE_OK) return s;
     }
     a.kind = kColsT;             // dW1[e] = Xs[seg]^T dZ[seg]
     a.A = ws + L.Xs; a.B = ws + L.dZ; a.C = dW1; a.K = D.d; a.Nout = D.h;
-    run_gemm(D, a, st);
+    { ScopedTimer tm(S_DW1, st); run_gemm(D, a, st); }
     if ((s = check_launch("expert layer 1 weight gradient")) != MOE_OK) return s;
 
-    launch_gate_bwd(D, L, ws + L.Xs, ws + L.dXs, Wg, (const float*)(ws + L.dl), plan->topk_idx, plan->pos,
-                    plan->perm, plan->counts, plan->offsets, dX, dWg, dbg, ws, st);
+    {
+        ScopedTimer tm(S_GATEBWD, st);
+        launch_gate_bwd(D, L, ws + L.Xs, ws + L.dXs, Wg, (const float*)(ws + L.dl), plan->topk_idx, plan->pos,
+                        plan->perm, plan->counts, plan->offsets, dX, dWg, dbg, ws, st);
+    }
     return check_launch("gate backward");
 }
 
