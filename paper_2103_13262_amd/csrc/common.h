@@ -24,6 +24,7 @@ struct WsLayout {
     size_t hist;      // [nb][E] int32: per plan-chunk histogram, then exclusive base inside the expert
     size_t dwg_part;  // [E][S][d] float: partial sums of dWg
     size_t dbg_part;  // [E][S] float
+    size_t zeros;     // 1 KB of zeros (written by the plan step): source of masked reduction rows
     size_t total;
     int nb;           // plan chunks = ceil(M / kPlanChunk)
     int S;            // row splits per expert for the dWg reduction
@@ -63,6 +64,7 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.S = dwg_splits(D);
     L.dwg_part = take((size_t)D.E * L.S * D.d * sizeof(float));
     L.dbg_part = take((size_t)D.E * L.S * sizeof(float));
+    L.zeros = take(1024);
     L.total = o;
     return L;
 }
@@ -112,11 +114,14 @@ struct GemmArgs {
     const int32_t* offsets;
     const int32_t* tileP;  // [4][E+1]
     const int32_t* order;  // [E]
+    const void* zeros;     // 1 KB of zeros
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT
+    int debug;        // development only: timing experiments (results invalid when non-zero)
 };
 void launch_ggemm_f32(const GemmArgs& a, hipStream_t st);
 void launch_ggemm_bf16(const GemmArgs& a, hipStream_t st);
+void launch_ggemm_bf16_dma(const GemmArgs& a, hipStream_t st);
 
 // ---- small device helpers ------------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }

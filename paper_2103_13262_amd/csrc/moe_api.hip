@@ -4,6 +4,7 @@
 // per-expert linear layers as grouped products, gather; and the reverse for the gradient.
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -128,7 +129,10 @@ static moe_status_t check_ws(const moe_desc_t* D, const void* ws, size_t bytes, 
 
 static void run_gemm(const moe_desc_t& D, GemmArgs& a, hipStream_t st)
 {
-    if (D.dtype == MOE_BF16) launch_ggemm_bf16(a, st);
+    static const int dbg = [] { const char* v = getenv("MOE355_DEBUG"); return v ? atoi(v) : 0; }();
+    a.debug = dbg;
+    static const bool legacy = [] { const char* v = getenv("MOE355_GEMM"); return v && !strcmp(v, "v1"); }();
+    if (D.dtype == MOE_BF16) { if (legacy) launch_ggemm_bf16(a, st); else launch_ggemm_bf16_dma(a, st); }
     else launch_ggemm_f32(a, st);
 }
 
@@ -258,6 +262,7 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     a.offsets = plan->offsets;
     a.tileP = (const int32_t*)(ws + L.tileP);
     a.order = (const int32_t*)(ws + L.order);
+    a.zeros = ws + L.zeros;
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
     a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h;
@@ -312,6 +317,7 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     a.offsets = plan->offsets;
     a.tileP = (const int32_t*)(ws + L.tileP);
     a.order = (const int32_t*)(ws + L.order);
+    a.zeros = ws + L.zeros;
     a.out_f32 = D.grad_dtype == MOE_F32;
     a.accumulate = D.accumulate;
 

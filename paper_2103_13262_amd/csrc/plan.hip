@@ -54,8 +54,10 @@ __device__ __forceinline__ int block_excl_scan_1024(int v, int* s_wave /*[16]*/,
 
 __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ hist, int nb, int E, long M,
                                                   int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-                                                  int32_t* __restrict__ tileP, int32_t* __restrict__ order)
+                                                  int32_t* __restrict__ tileP, int32_t* __restrict__ order,
+                                                  int32_t* __restrict__ zeros)
 {
+    if (threadIdx.x < 256) zeros[threadIdx.x] = 0;   // 1 KB page read in place of masked rows
     __shared__ int s_cnt[kMaxE];
     __shared__ int s_wave[16];
     const int e = threadIdx.x;
@@ -155,7 +157,8 @@ void launch_plan(const moe_desc_t& D, const WsLayout& L, const int32_t* topk_idx
     int nbits = 0;
     while ((1 << nbits) < D.E) ++nbits;
     if (L.nb > 0) hipLaunchKernelGGL(plan_hist, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, hist);
-    hipLaunchKernelGGL(plan_scan, dim3(1), dim3(1024), 0, st, hist, L.nb, D.E, M, counts, offsets, tileP, order);
+    hipLaunchKernelGGL(plan_scan, dim3(1), dim3(1024), 0, st, hist, L.nb, D.E, M, counts, offsets, tileP, order,
+                       (int32_t*)(ws + L.zeros));
     if (L.nb > 0)
         hipLaunchKernelGGL(plan_rank, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, nbits, (const int32_t*)hist,
                            (const int32_t*)offsets, pos, perm);
