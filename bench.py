@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=16)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C1", help="C0..C4 (C1 is the configuration the metric is quoted on)")
+    ap.add_argument("--custom", default=None, metavar="N,d,h,E,k[,zipf_s]",
+                    help="a bf16 layer of another shape (sweeps of experts / rows per expert); overrides --workload")
     ap.add_argument("--cpu-sample-tokens", type=int, default=-1, help="tokens of the oracle sample (0: skip)")
     return ap.parse_args()
 
@@ -65,6 +67,11 @@ def main():
         sys.exit(1)
     B.lib()   # raises if the HIP library has not been built: there is no fallback
     w = WORKLOADS[a.workload]
+    if a.custom:
+        from paper_2103_13262_amd.synth import Workload
+        f = a.custom.split(",")
+        w = Workload("custom", int(f[0]), int(f[1]), int(f[2]), int(f[3]), int(f[4]), "bf16",
+                     float(f[5]) if len(f) > 5 else 0.0, 20210313 * 10 + 9)
     inputs = make_inputs(w)
     dev = torch.device("cuda:0")
     bf = w.dtype == "bf16"

@@ -24,6 +24,7 @@ struct WsLayout {
     size_t hist;      // [nb][E] int32: per plan-chunk histogram, then exclusive base inside the expert
     size_t dwg_part;  // [E][S][d] float: partial sums of dWg
     size_t dbg_part;  // [E][S] float
+    size_t WgT;       // [E][d] gate matrix transposed (written by the backward pass), element type = desc.dtype
     size_t zeros;     // 1 KB of zeros (written by the plan step): source of masked reduction rows
     size_t total;
     int nb;           // plan chunks = ceil(M / kPlanChunk)
@@ -64,6 +65,7 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.S = dwg_splits(D);
     L.dwg_part = take((size_t)D.E * L.S * D.d * sizeof(float));
     L.dbg_part = take((size_t)D.E * L.S * sizeof(float));
+    L.WgT = take((size_t)D.E * D.d * b);
     L.zeros = take(1024);
     L.total = o;
     return L;
@@ -117,7 +119,8 @@ struct GemmArgs {
     const void* zeros;     // 1 KB of zeros
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT
-    int debug;        // development only: timing experiments (results invalid when non-zero)
+    int debug;        // development only: selects a tile configuration
+    long long* trace; // development only: per-workgroup phase timestamps (8 per workgroup) or NULL
 };
 void launch_ggemm_f32(const GemmArgs& a, hipStream_t st);
 void launch_ggemm_bf16(const GemmArgs& a, hipStream_t st);

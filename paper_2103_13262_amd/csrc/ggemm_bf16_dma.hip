@@ -18,7 +18,10 @@
 // Rows / columns outside the tile's valid extent are fetched from a clamped (valid) address and
 // their results are never stored.  Reduction rows past the end of an expert's segment (weight
 // gradients only) are fetched from a page of zeros.
+#include <cstdio>
+#include <cstdlib>
 #include <type_traits>
+#include <vector>
 
 #include "common.h"
 
@@ -33,9 +36,13 @@ typedef unsigned short u16;
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-constexpr int BK = 32;
-
-__device__ __forceinline__ int swz(int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); }
+// Chunk swizzle of k-contiguous tiles (row r, 16-byte chunk c sits at position c ^ swz(r)).
+//   BK = 32: 4 chunks per row;  BK = 64: 8 chunks per row.
+template <int BK> __device__ __forceinline__ int swz(int r)
+{
+    if constexpr (BK == 32) return ((r >> 1) & 3) ^ ((r >> 3) & 1);
+    else return (r >> 1) & 7;
+}
 
 // s_waitcnt vmcnt(N) only (export and LDS counters left at their maxima), gfx9 encoding.
 template <int N> __device__ __forceinline__ void wait_vmcnt()
@@ -52,8 +59,9 @@ template <int PER, int MAXG> __device__ __forceinline__ void wait_groups(int gro
     }
 }
 
-template <int KIND, int WM, int WN, int TM, int TN, int STAGES>
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK_>
 struct Cfg {
+    static constexpr int BK = BK_;
     static constexpr int NW = WM * WN, NT = NW * 64;
     static constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
     static constexpr bool A_TRANS = KIND == kColsT;
@@ -68,7 +76,7 @@ struct Cfg {
 //   !TRANS: src[row][k]; lane p of load j covers row j*16 + p/4, logical chunk (p&3) ^ swz(p/4).
 //    TRANS: src[k][row]; CPR = R/8 chunks per k-row; lane p of load j covers k-row j*(64/CPR) + p/CPR,
 //           logical chunk (p % CPR) ^ 2*(krow & 3).
-template <bool TRANS, int R, int NW, int L>
+template <bool TRANS, int R, int NW, int L, int BK>
 __device__ __forceinline__ void setup_ptrs(const u16* base, long ld, int valid, int wave, int lane, const u16* (&ptr)[L],
                                            int (&krow)[L])
 {
@@ -76,8 +84,9 @@ __device__ __forceinline__ void setup_ptrs(const u16* base, long ld, int valid, 
     for (int i = 0; i < L; ++i) {
         const int j = wave + i * NW;
         if constexpr (!TRANS) {
-            int row = j * 16 + (lane >> 2);
-            const int c = (lane & 3) ^ swz(lane >> 2);
+            constexpr int CK = BK / 8;                      // chunks per row; one load covers 64 / CK rows
+            int row = j * (64 / CK) + lane / CK;
+            const int c = (lane % CK) ^ swz<BK>(row);
             row = row < valid ? row : valid - 1;
             ptr[i] = base + (long)row * ld + c * 8;
             krow[i] = 0;
@@ -92,12 +101,14 @@ __device__ __forceinline__ void setup_ptrs(const u16* base, long ld, int valid, 
     }
 }
 
-template <int KIND, int WM, int WN, int TM, int TN, int STAGES>
-__global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int ntm, int ntn)
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK, int OCC>
+__global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g, int ntm, int ntn)
 {
-    using C = Cfg<KIND, WM, WN, TM, TN, STAGES>;
+    using C = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
     constexpr int BM = C::BM, BN = C::BN;
     extern __shared__ __align__(1024) char smem[];
+    long long ts[6];
+    ts[0] = wall_clock64();
 
     const u16* A;  long lda;
     const u16* B;  long ldb;
@@ -147,6 +158,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int
         Mt = min(BM, g.counts[e] - mt * BM);  Nt = min(BN, g.Nout - n0);  Kt = g.K;
     }
 
+    ts[1] = wall_clock64();
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
     const int wm = wave / WN, wn = wave % WN;
@@ -155,8 +167,8 @@ __global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int
     // ---- global -> LDS streams ----
     const u16* pa[C::LA]; int ka[C::LA];
     const u16* pb[C::LB]; int kb[C::LB];
-    setup_ptrs<C::A_TRANS, BM, C::NW, C::LA>(A, lda, Mt, wave, lane, pa, ka);
-    setup_ptrs<C::B_TRANS, BN, C::NW, C::LB>(B, ldb, Nt, wave, lane, pb, kb);
+    setup_ptrs<C::A_TRANS, BM, C::NW, C::LA, BK>(A, lda, Mt, wave, lane, pa, ka);
+    setup_ptrs<C::B_TRANS, BN, C::NW, C::LB, BK>(B, ldb, Nt, wave, lane, pb, kb);
     const long stepA = C::A_TRANS ? (long)BK * lda : BK, stepB = C::B_TRANS ? (long)BK * ldb : BK;
     const u16* zeros = (const u16*)g.zeros + lane * 8;
 
@@ -191,7 +203,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int
     for (int i = 0; i < TM; ++i) {
         const int rb = (wm * TM + i) * 32;
         if constexpr (!C::A_TRANS) {
-            offA[i] = (rb + (lane & 31)) * 64 + ((((lane >> 5)) ^ swz(lane & 15)) << 4);
+            offA[i] = (rb + (lane & 31)) * (BK * 2) + ((((lane >> 5)) ^ swz<BK>(lane & 31)) << 4);
         } else {
             const int s = lane & 15, col = rb + ((lane >> 4) & 1) * 16 + 4 * (s & 3);
             offA[i] = ((lane >> 5) * 8 + (s >> 2)) * (BM * 2) + ((((col >> 3)) ^ (2 * (s >> 2))) << 4) + (col & 7) * 2;
@@ -201,7 +213,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int
     for (int j = 0; j < TN; ++j) {
         const int rb = (wn * TN + j) * 32;
         if constexpr (!C::B_TRANS) {
-            offB[j] = (rb + (lane & 31)) * 64 + ((((lane >> 5)) ^ swz(lane & 15)) << 4);
+            offB[j] = (rb + (lane & 31)) * (BK * 2) + ((((lane >> 5)) ^ swz<BK>(lane & 31)) << 4);
         } else {
             const int s = lane & 15, col = rb + ((lane >> 4) & 1) * 16 + 4 * (s & 3);
             offB[j] = ((lane >> 5) * 8 + (s >> 2)) * (BN * 2) + ((((col >> 3)) ^ (2 * (s >> 2))) << 4) + (col & 7) * 2;
@@ -249,7 +261,9 @@ __global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int
     auto main_loop = [&](auto full_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
         constexpr int PER = C::LA + C::LB;
-        bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+        static_assert((BK / 16) % 2 == 0, "even number of MFMA steps per block");
+        constexpr int KS = BK / 16;                         // 16-deep MFMA steps per block (even)
+        bf16x8 fa[2][TM], fb[2][TN];                        // operand registers, double-buffered by step parity
         auto fetch = [&](int slot, int ks, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
             const char* tA = smem + slot * C::STAGE_BYTES;
             const char* tB = tA + C::A_BYTES;
@@ -274,20 +288,32 @@ __global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int
             if (s < nk) issue(s);
         wait_groups<PER, STAGES - 1>(min(nk - 1, STAGES - 1));   // block 0 has landed
         __builtin_amdgcn_s_barrier();
-        fetch(0, 0, a0, b0);
-        for (int kt = 0; kt < nk; ++kt) {
-            fetch(kt % STAGES, 1, a1, b1);
-            mma(a0, b0);
-            if (kt + 1 < nk) {
-                // own loads of block kt+1 have landed (blocks kt+2 .. may stay in flight) and own LDS
-                // reads of block kt are complete; after the barrier that holds for every wave
-                wait_groups<PER, STAGES - 2>(min(nk - 2 - kt, STAGES - 2));
-                __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), other counters untouched
-                __builtin_amdgcn_s_barrier();
-                if (kt + STAGES < nk) issue(kt + STAGES);
-                fetch((kt + 1) % STAGES, 0, a0, b0);
+        ts[2] = wall_clock64();
+        fetch(0, 0, fa[0], fb[0]);
+        for (int kt = 0; kt + 1 < nk; ++kt) {
+            const int slot = kt % STAGES;
+#pragma unroll
+            for (int ks = 0; ks < KS - 1; ++ks) {
+                fetch(slot, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+                mma(fa[ks & 1], fb[ks & 1]);
             }
-            mma(a1, b1);
+            // own loads of block kt+1 have landed (blocks kt+2 .. may stay in flight) and own LDS
+            // reads of block kt are complete; after the barrier that holds for every wave
+            wait_groups<PER, STAGES - 2>(min(nk - 2 - kt, STAGES - 2));
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), other counters untouched
+            __builtin_amdgcn_s_barrier();
+            if (kt + STAGES < nk) issue(kt + STAGES);
+            fetch((kt + 1) % STAGES, 0, fa[0], fb[0]);
+            mma(fa[1], fb[1]);
+        }
+        {   // last block: nothing left to prefetch
+            const int slot = (nk - 1) % STAGES;
+#pragma unroll
+            for (int ks = 0; ks < KS - 1; ++ks) {
+                fetch(slot, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+                mma(fa[ks & 1], fb[ks & 1]);
+            }
+            mma(fa[1], fb[1]);
         }
     };
     if (tm_act == TM) main_loop(std::true_type{});
@@ -300,6 +326,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int
     constexpr int PITCH = TN * 32 + 4;                       // floats; rows 4 apart land in different banks
     static_assert(C::NW * 32 * PITCH * 4 <= C::SMEM, "epilogue patch must fit in the ring");
     __syncthreads();                                         // all waves are done with the ring
+    ts[3] = wall_clock64();
     float* patch = (float*)smem + wave * (32 * PITCH);
     constexpr int CPRW = TN * 4;                             // 8-column pieces per row of the wave tile
     const int ldc = g.Nout;
@@ -370,41 +397,87 @@ __global__ __launch_bounds__(WM * WN * 64) void ggemm_dma_kernel(GemmArgs g, int
             }
         }
     }
+    if (g.trace && threadIdx.x == 0) {
+        ts[4] = wall_clock64();
+        long long* t = g.trace + (size_t)blockIdx.x * 8;
+        t[0] = ts[0]; t[1] = ts[1]; t[2] = ts[2]; t[3] = ts[3]; t[4] = ts[4]; t[5] = nk; t[6] = tm_act; t[7] = 1;
+    }
 }
 
-template <int KIND, int WM, int WN, int TM, int TN, int STAGES> void launch_cfg(const GemmArgs& a, hipStream_t st)
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK, int OCC = 1>
+void launch_cfg(const GemmArgs& a, hipStream_t st)
 {
-    using C = Cfg<KIND, WM, WN, TM, TN, STAGES>;
-    auto kern = ggemm_dma_kernel<KIND, WM, WN, TM, TN, STAGES>;
+    using C = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
+    auto kern = ggemm_dma_kernel<KIND, WM, WN, TM, TN, STAGES, BK, OCC>;
     static bool attr_set = false;   // the LDS ring is larger than the default dynamic limit
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM) != hipSuccess)
             return;   // launch skipped; the caller's hipGetLastError() reports the failure
         attr_set = true;
     }
+    long blocks;
+    int ntm = 0, ntn = (a.Nout + C::BN - 1) / C::BN;
     if (KIND == kColsT) {
-        const int ntm = (a.K + C::BM - 1) / C::BM, ntn = (a.Nout + C::BN - 1) / C::BN;
-        const long blocks = (long)a.E * ntm * ntn;
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(C::NT), C::SMEM, st, a, ntm, ntn);
+        ntm = (a.K + C::BM - 1) / C::BM;
+        blocks = (long)a.E * ntm * ntn;
     } else {
-        const int ntn = (a.Nout + C::BN - 1) / C::BN;
         const long max_tiles = (a.M / C::BM + a.E) * ntn;
-        const long blocks = (max_tiles + 7) / 8 * 8;
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(C::NT), C::SMEM, st, a, 0, ntn);
+        blocks = (max_tiles + 7) / 8 * 8;
+    }
+    static const bool trace_on = getenv("MOE355_TRACE") != nullptr;   // development only
+    GemmArgs b = a;
+    if (trace_on) {
+        static long long* buf = nullptr;
+        if (!buf) (void)hipMalloc(&buf, 8 * sizeof(long long) * 65536);
+        b.trace = blocks <= 65536 ? buf : nullptr;
+        if (b.trace) (void)hipMemsetAsync(buf, 0, 8 * sizeof(long long) * blocks, st);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(C::NT), C::SMEM, st, b, ntm, ntn);
+    if (trace_on && b.trace) {
+        std::vector<long long> h(8 * blocks);
+        (void)hipStreamSynchronize(st);
+        (void)hipMemcpy(h.data(), b.trace, h.size() * sizeof(long long), hipMemcpyDeviceToHost);
+        double ph[4] = {0, 0, 0, 0}; long n = 0, nfull = 0; long long tmin = 0, tmax = 0;
+        for (long i = 0; i < blocks; ++i) {
+            const long long* t = &h[8 * i];
+            if (!t[7]) continue;
+            if (!n || t[0] < tmin) tmin = t[0];
+            if (!n || t[4] > tmax) tmax = t[4];
+            ++n;
+            if (t[6] != TM) continue;
+            ++nfull;
+            for (int k = 0; k < 4; ++k) ph[k] += (double)(t[k + 1] - t[k]);
+        }
+        fprintf(stderr, "[trace kind %d cfg %dx%dx%d] blocks %ld active %ld full %ld span %.1f us | per full tile (us): decode %.2f "
+                "prologue %.2f mainloop %.2f epilogue %.2f\n", KIND, C::BM, C::BN, BK, blocks, n, nfull, (tmax - tmin) * 0.01,
+                ph[0] / nfull * 0.01, ph[1] / nfull * 0.01, ph[2] / nfull * 0.01, ph[3] / nfull * 0.01);
     }
 }
 
+template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
+{
+    switch (a.debug) {   // development switch between tile configurations
+        case 1: launch_cfg<KIND, 2, 2, 4, 4, 2, 64>(a, st); break;   // 256x256, BK 64, 2 stages
+        case 2: launch_cfg<KIND, 2, 2, 4, 2, 3, 64>(a, st); break;   // 256x128, BK 64, 3 stages
+        case 3: launch_cfg<KIND, 2, 4, 4, 2, 4, 32>(a, st); break;   // 256x256, 8 waves, BK 32, 4 stages
+        case 4: launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st); break;   // 256x256, 8 waves, BK 64, 2 stages
+        case 5: launch_cfg<KIND, 2, 2, 4, 2, 3, 32, 2>(a, st); break; // 256x128, 4 waves, BK 32, 3 stages, 2 workgroups per CU
+        case 6: launch_cfg<KIND, 2, 2, 2, 4, 3, 32, 2>(a, st); break; // 128x256, same
+        case 7: launch_cfg<KIND, 2, 2, 4, 2, 2, 32, 3>(a, st); break; // 256x128, 2 stages, 3 workgroups per CU
+        default: launch_cfg<KIND, 2, 2, 4, 4, 4, 32>(a, st); break;  // 256x256, BK 32, 4 stages
+    }
+}
 }  // namespace dma
 
 void launch_ggemm_bf16_dma(const GemmArgs& a, hipStream_t st)
 {
     using namespace dma;
     switch (a.kind) {
-        case kRowsNN_GeLU: launch_cfg<kRowsNN_GeLU, 2, 2, 4, 4, 4>(a, st); break;
-        case kRowsNN: launch_cfg<kRowsNN, 2, 2, 4, 4, 4>(a, st); break;
-        case kRowsNT_dGeLU: launch_cfg<kRowsNT_dGeLU, 2, 2, 4, 4, 4>(a, st); break;
-        case kRowsNT: launch_cfg<kRowsNT, 2, 2, 4, 4, 4>(a, st); break;
-        default: launch_cfg<kColsT, 2, 2, 4, 4, 4>(a, st); break;
+        case kRowsNN_GeLU: launch_kind<kRowsNN_GeLU>(a, st); break;
+        case kRowsNN: launch_kind<kRowsNN>(a, st); break;
+        case kRowsNT_dGeLU: launch_kind<kRowsNT_dGeLU>(a, st); break;
+        case kRowsNT: launch_kind<kRowsNT>(a, st); break;
+        default: launch_kind<kColsT>(a, st); break;
     }
 }
 

@@ -125,12 +125,23 @@ __global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY
     }
 }
 
+// ---- WgT[e][i] = Wg[i][e]: lets the kernel below read a gate column as contiguous 16-byte pieces ----
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_gate(const T* __restrict__ Wg, T* __restrict__ WgT, int d, int E)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;   // index into WgT
+    if (i < (long)d * E) {
+        const int e = (int)(i / d), row = (int)(i % d);
+        WgT[i] = Wg[(size_t)row * E + e];
+    }
+}
+
 // ---- dX[t,:] = sum_j dXs[pos[a],:] + sum_j dl[a] * Wg[:, idx[a]] ------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs, const T* __restrict__ Wg,
+__global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs, const void* __restrict__ WgT,
                                                    const float* __restrict__ dl, const int32_t* __restrict__ topk_idx,
                                                    const int32_t* __restrict__ pos, void* __restrict__ dX, long N, int k,
-                                                   int E, int cpr)
+                                                   int cpr)
 {
     constexpr int V = Vec<T>::N;
     const long total = N * cpr;
@@ -149,14 +160,10 @@ __global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs,
         for (int j = 0; j < k; ++j) {
             const long a = t * k + j;
             const float g = dl[a];
-            const int e = topk_idx[a];
+            float wv[V];
+            Vec<T>::load(WgT, (size_t)topk_idx[a] * cpr + c, wv);
 #pragma unroll
-            for (int u = 0; u < V; ++u) {
-                const T wv = Wg[(size_t)(c * V + u) * E + e];
-                float wf;
-                if constexpr (sizeof(T) == 2) wf = bf16_to_f32(wv); else wf = wv;
-                acc[u] = fmaf(g, wf, acc[u]);
-            }
+            for (int u = 0; u < V; ++u) acc[u] = fmaf(g, wv[u], acc[u]);
         }
         Vec<T>::store(dX, (size_t)i, acc);
     }
@@ -275,8 +282,11 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     const dim3 pg(D.E, L.S, (cpr + 127) / 128);
     const unsigned fg = (unsigned)(((long)D.d * D.E + 255) / 256);
     const unsigned xg = grid_for((long)D.N * cpr);
+    const unsigned tg = (unsigned)(((long)D.d * D.E + 255) / 256);
+    void* WgT = ws + L.WgT;
     if (D.dtype == MOE_BF16) {
         using T = unsigned short;
+        hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
         hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, part, bpart, L.S, D.d, cpr);
         if (D.grad_dtype == MOE_BF16)
             hipLaunchKernelGGL(dwg_final<unsigned short>, dim3(fg), dim3(256), 0, st, (const float*)part,
@@ -284,15 +294,16 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
         else
             hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
                                (float*)dWg, dbg, L.S, D.d, D.E, D.accumulate);
-        hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const T*)Wg, dl, topk_idx, pos, dX,
-                           (long)D.N, D.k, D.E, cpr);
+        hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
+                           (long)D.N, D.k, cpr);
     } else {
         using T = float;
+        hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
         hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, part, bpart, L.S, D.d, cpr);
         hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
                            (float*)dWg, dbg, L.S, D.d, D.E, D.accumulate);
-        hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const T*)Wg, dl, topk_idx, pos, dX,
-                           (long)D.N, D.k, D.E, cpr);
+        hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
+                           (long)D.N, D.k, cpr);
     }
 }
 
