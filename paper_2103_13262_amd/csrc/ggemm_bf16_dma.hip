@@ -72,7 +72,8 @@ struct Cfg {
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile must split evenly over waves");
 };
 
-// Per-lane source pointers of one operand for reduction block 0 (advanced by the caller).
+// Per-lane source pointers of one operand for reduction block 0 (advanced by the caller) and the
+// reduction offset inside a block that the lane's chunk starts at (krow).
 //   !TRANS: src[row][k]; lane p of load j covers row j*16 + p/4, logical chunk (p&3) ^ swz(p/4).
 //    TRANS: src[k][row]; CPR = R/8 chunks per k-row; lane p of load j covers k-row j*(64/CPR) + p/CPR,
 //           logical chunk (p % CPR) ^ 2*(krow & 3).
@@ -89,7 +90,7 @@ __device__ __forceinline__ void setup_ptrs(const u16* base, long ld, int valid, 
             const int c = (lane % CK) ^ swz<BK>(row);
             row = row < valid ? row : valid - 1;
             ptr[i] = base + (long)row * ld + c * 8;
-            krow[i] = 0;
+            krow[i] = c * 8;            // reduction offset of this lane's chunk inside a block
         } else {
             constexpr int CPR = R / 8;
             const int kr = j * (64 / CPR) + lane / CPR;
@@ -171,6 +172,9 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
     setup_ptrs<C::B_TRANS, BN, C::NW, C::LB, BK>(B, ldb, Nt, wave, lane, pb, kb);
     const long stepA = C::A_TRANS ? (long)BK * lda : BK, stepB = C::B_TRANS ? (long)BK * ldb : BK;
     const u16* zeros = (const u16*)g.zeros + lane * 8;
+    // reduction indices past Kt are read from the zero page: always possible for the weight gradients (Kt = rows
+    // of the expert), and for the other kinds only when a block is deeper than the 32 that divides every width
+    constexpr bool KMASK = KIND == kColsT || BK > 32;
 
     // The loads are written as inline assembly so that the compiler does not serialise them against
     // the LDS reads of other ring slots (it cannot tell the slots apart and would wait for all loads
@@ -182,7 +186,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
 #pragma unroll
         for (int i = 0; i < C::LA; ++i) {
             const u16* src = pa[i];
-            if constexpr (KIND == kColsT) src = (kt * BK + ka[i] < Kt) ? src : zeros;
+            if constexpr (KMASK) src = (kt * BK + ka[i] < Kt) ? src : zeros;
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                          :: "s"(sA + i * C::NW * 1024), "v"(src) : "memory");
             pa[i] += stepA;
@@ -190,7 +194,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
 #pragma unroll
         for (int i = 0; i < C::LB; ++i) {
             const u16* src = pb[i];
-            if constexpr (KIND == kColsT) src = (kt * BK + kb[i] < Kt) ? src : zeros;
+            if constexpr (KMASK) src = (kt * BK + kb[i] < Kt) ? src : zeros;
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                          :: "s"(sB + i * C::NW * 1024), "v"(src) : "memory");
             pb[i] += stepB;
@@ -460,11 +464,11 @@ template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
         case 1: launch_cfg<KIND, 2, 2, 4, 4, 2, 64>(a, st); break;   // 256x256, BK 64, 2 stages
         case 2: launch_cfg<KIND, 2, 2, 4, 2, 3, 64>(a, st); break;   // 256x128, BK 64, 3 stages
         case 3: launch_cfg<KIND, 2, 4, 4, 2, 4, 32>(a, st); break;   // 256x256, 8 waves, BK 32, 4 stages
-        case 4: launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st); break;   // 256x256, 8 waves, BK 64, 2 stages
+        case 8: launch_cfg<KIND, 2, 2, 4, 4, 4, 32>(a, st); break;   // 256x256, 4 waves, BK 32, 4 stages
         case 5: launch_cfg<KIND, 2, 2, 4, 2, 3, 32, 2>(a, st); break; // 256x128, 4 waves, BK 32, 3 stages, 2 workgroups per CU
         case 6: launch_cfg<KIND, 2, 2, 2, 4, 3, 32, 2>(a, st); break; // 128x256, same
         case 7: launch_cfg<KIND, 2, 2, 4, 2, 2, 32, 3>(a, st); break; // 256x128, 2 stages, 3 workgroups per CU
-        default: launch_cfg<KIND, 2, 2, 4, 4, 4, 32>(a, st); break;  // 256x256, BK 32, 4 stages
+        default: launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st); break;  // 256x256, 8 waves, BK 64, 2 stages
     }
 }
 }  // namespace dma
