@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libmoe355.so")
 SOURCES = ["moe_api.hip", "gate_topk.hip", "plan.hip", "rowmove.hip", "ggemm_f32.hip", "ggemm_bf16.hip", "ggemm_bf16_dma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+    "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall",
     # packed-fp32 VALU forms are kept out of all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",

@@ -135,10 +135,49 @@ __device__ __forceinline__ unsigned short f32_to_bf16(float f)
     u += 0x7fffu + ((u >> 16) & 1u);                                                  // round to nearest even
     return (unsigned short)(u >> 16);
 }
+// Two floats -> two bf16 (round to nearest even) in one 32-bit word, low half = a: one v_cvt_pk_bf16_f32.
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
+{
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
 __device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_grad_f(float z)
 {
     return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * __expf(-0.5f * z * z) * 0.39894228040143268f;
+}
+
+
+// Branch-free GeLU and GeLU' for the bf16 epilogues.  erf by the rational-exponential form of Abramowitz &
+// Stegun 7.1.26 (|error| <= 1.5e-7, far below bf16 resolution): erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2),
+// t = 1 / (1 + p x) for x >= 0, odd extension for x < 0.
+__device__ __forceinline__ float erf_fast(float x)
+{
+    const float ax = fabsf(x);
+    const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
+    float poly = fmaf(1.061405429f, t, -1.453152027f);
+    poly = fmaf(poly, t, 1.421413741f);
+    poly = fmaf(poly, t, -0.284496736f);
+    poly = fmaf(poly, t, 0.254829592f);
+    const float e = __expf(-ax * ax);
+    const float r = fmaf(-poly * t, e, 1.0f);
+    return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_fast(float z) { return 0.5f * z * (1.0f + erf_fast(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_fast(float z)
+{   // Phi(z) + z phi(z); the exponential of the erf formula at x = z / sqrt(2) is exp(-z^2 / 2), shared with phi
+    const float ax = fabsf(z) * 0.70710678118654752f;
+    const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
+    float poly = fmaf(1.061405429f, t, -1.453152027f);
+    poly = fmaf(poly, t, 1.421413741f);
+    poly = fmaf(poly, t, -0.284496736f);
+    poly = fmaf(poly, t, 0.254829592f);
+    const float e = __expf(-0.5f * z * z);
+    const float erf_abs = fmaf(-poly * t, e, 1.0f);
+    const float cdf = fmaf(0.5f, copysignf(erf_abs, z), 0.5f);
+    return fmaf(z * 0.39894228040143268f, e, cdf);
 }
 
 }  // namespace moe

@@ -21,6 +21,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>
+#include <utility>
 #include <vector>
 
 #include "common.h"
@@ -148,7 +149,25 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
         const int e = lo;
         const int mte = P[e + 1] - P[e];
         const int local = (int)(L - (long)P[e] * ntn);
-        const int nt = local / mte, mt = local - nt * mte;
+        // Order inside an expert: groups of up to GM row blocks; inside a group the row block runs fastest,
+        // then the column block.  Tiles that run at the same time on one XCD then form a patch that shares
+        // both the activation panels (across its column blocks) and the weight panels (across its row blocks).
+        constexpr int GM = 8;
+        int nt, mt;
+        {
+            const int full = mte / GM, per_group = GM * ntn;
+            const int gi = local / per_group;
+            if (gi < full) {
+                const int r = local - gi * per_group;
+                nt = r / GM;
+                mt = gi * GM + (r - nt * GM);
+            } else {
+                const int rem = mte - full * GM;
+                const int r = local - full * per_group;
+                nt = r / rem;
+                mt = full * GM + (r - nt * rem);
+            }
+        }
         const long r0 = (long)g.offsets[e] + (long)mt * BM;
         const int n0 = nt * BN;
         A = (const u16*)g.A + r0 * g.K;  lda = g.K;
@@ -180,27 +199,31 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
     // the LDS reads of other ring slots (it cannot tell the slots apart and would wait for all loads
     // before every read); the ordering is enforced by the explicit vmcnt waits and barriers below.
     const unsigned lds_base = (unsigned)(uintptr_t)LDS_PTR(char, smem);
-    auto issue = [&](int kt) {   // loads of reduction block kt into ring slot kt % STAGES
+    // One wave-level load (index l of the LA + LB loads this wave owns per block) of reduction block kt
+    // into ring slot kt % STAGES.  l is a compile-time constant at every call site.
+    auto issue_one = [&](int kt, auto lc) {
+        constexpr int l = decltype(lc)::value;
         const unsigned sA = lds_base + (kt % STAGES) * C::STAGE_BYTES + wave * 1024;
-        const unsigned sB = sA + C::A_BYTES;
-#pragma unroll
-        for (int i = 0; i < C::LA; ++i) {
-            const u16* src = pa[i];
-            if constexpr (KMASK) src = (kt * BK + ka[i] < Kt) ? src : zeros;
+        if constexpr (l < C::LA) {
+            const u16* src = pa[l];
+            if constexpr (KMASK) src = (kt * BK + ka[l] < Kt) ? src : zeros;
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(sA + i * C::NW * 1024), "v"(src) : "memory");
-            pa[i] += stepA;
-        }
-#pragma unroll
-        for (int i = 0; i < C::LB; ++i) {
+                         :: "s"(sA + l * C::NW * 1024), "v"(src) : "memory");
+            pa[l] += stepA;
+        } else {
+            constexpr int i = l - C::LA;
             const u16* src = pb[i];
             if constexpr (KMASK) src = (kt * BK + kb[i] < Kt) ? src : zeros;
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(sB + i * C::NW * 1024), "v"(src) : "memory");
+                         :: "s"(sA + C::A_BYTES + i * C::NW * 1024), "v"(src) : "memory");
             pb[i] += stepB;
         }
     };
-
+    auto issue = [&](int kt) {   // all loads of block kt at once (prologue)
+        [&]<int... L>(std::integer_sequence<int, L...>) {
+            (issue_one(kt, std::integral_constant<int, L>{}), ...);
+        }(std::make_integer_sequence<int, C::LA + C::LB>{});
+    };
     // ---- per-lane LDS offsets of the MFMA operand fetches (within one operand tile, ks = 0) ----
     int offA[TM], offB[TN];
 #pragma unroll
@@ -277,14 +300,25 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
             for (int i = 0; i < TM; ++i)
                 if (FULL || i < tm_act) a[i] = fetchA(tA, i, ks);
         };
-        auto mma = [&](const bf16x8 (&a)[TM], const bf16x8 (&b)[TN]) {
+        // One 16-deep MFMA step.  The loads of the block that refills the slot freed at the last barrier
+        // are spread over the KS steps that follow that barrier (SLOTS = KS * TM places, one before each
+        // accumulator row), so that they do not hold up the matrix cores in one burst.
+        constexpr int SLOTS = KS * TM;
+        auto mma = [&](const bf16x8 (&a)[TM], const bf16x8 (&b)[TN], auto step_c, int load_kt) {
+            constexpr int STEP = decltype(step_c)::value;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i) {
+                if (load_kt >= 0) {
+                    [&]<int... L>(std::integer_sequence<int, L...>) {
+                        ((L * SLOTS / PER == STEP * TM + i ? (issue_one(load_kt, std::integral_constant<int, L>{}), 0) : 0), ...);
+                    }(std::make_integer_sequence<int, PER>{});
+                }
                 if (FULL || i < tm_act) {
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
                 }
+            }
         };
         if (nk == 0) return;
 #pragma unroll
@@ -294,31 +328,26 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
         __builtin_amdgcn_s_barrier();
         ts[2] = wall_clock64();
         fetch(0, 0, fa[0], fb[0]);
+        int load_kt = -1;   // block being loaded piecewise (into the slot freed at the last barrier), or -1
+        auto steps_before_barrier = [&](int slot) {   // steps 0 .. KS-2 of a block: load pieces 1 .. KS-1
+            [&]<int... S>(std::integer_sequence<int, S...>) {
+                ((fetch(slot, S + 1, fa[(S + 1) & 1], fb[(S + 1) & 1]),
+                  mma(fa[S & 1], fb[S & 1], std::integral_constant<int, S + 1>{}, load_kt)), ...);
+            }(std::make_integer_sequence<int, KS - 1>{});
+        };
         for (int kt = 0; kt + 1 < nk; ++kt) {
-            const int slot = kt % STAGES;
-#pragma unroll
-            for (int ks = 0; ks < KS - 1; ++ks) {
-                fetch(slot, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-                mma(fa[ks & 1], fb[ks & 1]);
-            }
+            steps_before_barrier(kt % STAGES);
             // own loads of block kt+1 have landed (blocks kt+2 .. may stay in flight) and own LDS
             // reads of block kt are complete; after the barrier that holds for every wave
             wait_groups<PER, STAGES - 2>(min(nk - 2 - kt, STAGES - 2));
             __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), other counters untouched
             __builtin_amdgcn_s_barrier();
-            if (kt + STAGES < nk) issue(kt + STAGES);
+            load_kt = kt + STAGES < nk ? kt + STAGES : -1;
             fetch((kt + 1) % STAGES, 0, fa[0], fb[0]);
-            mma(fa[1], fb[1]);
+            mma(fa[1], fb[1], std::integral_constant<int, 0>{}, load_kt);
         }
-        {   // last block: nothing left to prefetch
-            const int slot = (nk - 1) % STAGES;
-#pragma unroll
-            for (int ks = 0; ks < KS - 1; ++ks) {
-                fetch(slot, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-                mma(fa[ks & 1], fb[ks & 1]);
-            }
-            mma(fa[1], fb[1]);
-        }
+        steps_before_barrier((nk - 1) % STAGES);   // last block: load_kt is -1 here, nothing left to prefetch
+        mma(fa[1], fb[1], std::integral_constant<int, 0>{}, -1);
     };
     if (tm_act == TM) main_loop(std::true_type{});
     else main_loop(std::false_type{});   // tail tiles skip the 32-row blocks that hold no valid row
@@ -352,10 +381,8 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
             float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
             const size_t o = c_off + (size_t)row * ldc + col;
             auto pack = [](const float* f) {
-                return make_uint4((unsigned)f32_to_bf16(f[0]) | ((unsigned)f32_to_bf16(f[1]) << 16),
-                                  (unsigned)f32_to_bf16(f[2]) | ((unsigned)f32_to_bf16(f[3]) << 16),
-                                  (unsigned)f32_to_bf16(f[4]) | ((unsigned)f32_to_bf16(f[5]) << 16),
-                                  (unsigned)f32_to_bf16(f[6]) | ((unsigned)f32_to_bf16(f[7]) << 16));
+                return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                                  pack_bf16x2(f[6], f[7]));
             };
             auto unpack = [](const uint4 u, float* f) {
                 const unsigned w[4] = {u.x, u.y, u.z, u.w};
@@ -368,13 +395,13 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void ggemm_dma_kernel(GemmArgs g
             if constexpr (KIND == kRowsNN_GeLU) {
                 *(uint4*)((u16*)g.C + o) = pack(x);
 #pragma unroll
-                for (int t = 0; t < 8; ++t) x[t] = gelu_f(x[t]);
+                for (int t = 0; t < 8; ++t) x[t] = gelu_fast(x[t]);
                 *(uint4*)((u16*)g.C2 + o) = pack(x);
             } else if constexpr (KIND == kRowsNT_dGeLU) {
                 float z[8];
                 unpack(*(const uint4*)((const u16*)g.Zin + o), z);
 #pragma unroll
-                for (int t = 0; t < 8; ++t) x[t] *= gelu_grad_f(z[t]);
+                for (int t = 0; t < 8; ++t) x[t] *= gelu_grad_fast(z[t]);
                 *(uint4*)((u16*)g.C + o) = pack(x);
             } else if constexpr (KIND == kColsT) {
                 if (g.out_f32) {
@@ -465,6 +492,11 @@ template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
         case 2: launch_cfg<KIND, 2, 2, 4, 2, 3, 64>(a, st); break;   // 256x128, BK 64, 3 stages
         case 3: launch_cfg<KIND, 2, 4, 4, 2, 4, 32>(a, st); break;   // 256x256, 8 waves, BK 32, 4 stages
         case 8: launch_cfg<KIND, 2, 2, 4, 4, 4, 32>(a, st); break;   // 256x256, 4 waves, BK 32, 4 stages
+        case 9: launch_cfg<KIND, 2, 4, 4, 2, 5, 32>(a, st); break;   // 256x256, 8 waves, BK 32, 5 stages (160 KB)
+        case 10: launch_cfg<KIND, 2, 2, 4, 4, 5, 32>(a, st); break;  // 256x256, 4 waves, BK 32, 5 stages (160 KB)
+        case 11: launch_cfg<KIND, 4, 2, 2, 2, 3, 64>(a, st); break;  // 256x128, 8 waves (64x64 each), BK 64, 3 stages
+        case 12: launch_cfg<KIND, 2, 4, 4, 1, 3, 64>(a, st); break;  // 256x128, 8 waves (128x32 each), BK 64, 3 stages
+        case 13: launch_cfg<KIND, 2, 2, 4, 2, 3, 64>(a, st); break;  // 256x128, 4 waves (128x64 each), BK 64, 3 stages
         case 5: launch_cfg<KIND, 2, 2, 4, 2, 3, 32, 2>(a, st); break; // 256x128, 4 waves, BK 32, 3 stages, 2 workgroups per CU
         case 6: launch_cfg<KIND, 2, 2, 2, 4, 3, 32, 2>(a, st); break; // 128x256, same
         case 7: launch_cfg<KIND, 2, 2, 4, 2, 2, 32, 3>(a, st); break; // 256x128, 2 stages, 3 workgroups per CU

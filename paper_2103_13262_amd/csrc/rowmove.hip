@@ -24,7 +24,7 @@ template <> struct Vec<unsigned short> {
     {
         unsigned w[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = (unsigned)f32_to_bf16(f[2 * i]) | ((unsigned)f32_to_bf16(f[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
         ((uint4*)base)[chunk] = make_uint4(w[0], w[1], w[2], w[3]);
     }
 };
