@@ -6,6 +6,7 @@
 // order starting from the bias: the products of two fp32-representable numbers are exact in
 // fp64, so the selection is that of exact arithmetic (ties -> lower expert id) up to fp64
 // summation rounding (~1e-16 relative; equal columns of the gate matrix still give equal logits).  Selection is k rounds of a butterfly arg-max over the group.
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -184,21 +185,169 @@ static void launch_typed(const moe_desc_t& D, const T* X, const T* Wg, const flo
     };
     using std::integral_constant;
 #define IC(v) integral_constant<int, v>{}
-    if (R <= 1) { if (tpw == 4) go(IC(1), IC(4)); else if (tpw == 2) go(IC(1), IC(2)); else go(IC(1), IC(1)); }
-    else if (R <= 2) { if (tpw == 4) go(IC(2), IC(4)); else if (tpw == 2) go(IC(2), IC(2)); else go(IC(2), IC(1)); }
-    else if (R <= 4) { if (tpw == 2) go(IC(4), IC(2)); else go(IC(4), IC(1)); }
-    else if (R <= 8) go(IC(8), IC(1));
-    else go(IC(16), IC(1));
+    if (tpw == 4) go(IC(1), IC(4)); else if (tpw == 2) go(IC(1), IC(2)); else go(IC(1), IC(1));   // E <= 16: R = 1
 #undef IC
+}
+
+// Sorted list of the k best (value, expert) pairs of one token, kept in registers.
+__device__ __forceinline__ void topk_insert(double cv, int ce, double (&v)[kMaxK], int (&id)[kMaxK], int k)
+{   // keeps v descending, equal values by ascending expert id
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j) {
+        if (j < k && (cv > v[j] || (cv == v[j] && ce < id[j]))) {
+            const double tv = v[j]; v[j] = cv; cv = tv;
+            const int ti = id[j]; id[j] = ce; ce = ti;
+        }
+    }
+}
+
+// ---- matrix-core variant: logits as an fp64 product on v_mfma_f64_16x16x4_f64 -------------------------
+// Workgroup = 64 tokens (16 per wavefront) x blocks of 64 experts.  Token features and gate columns are widened
+// to fp64 while they are staged into LDS (feature-major, 32 features per slab); every 4-deep step is one LDS
+// read for the token operand and one per 16 experts for the gate operand.  Operand lane l holds row/column
+// l%16 at depth l/16; result register r of lane l is token 4r + l/16, expert l%16.  The logits of a block are
+// passed through LDS and scanned token-per-lane (16 experts per wavefront) into sorted k-lists.
+typedef __attribute__((ext_vector_type(4))) double f64x4;
+
+template <typename T, int NT>
+__global__ __launch_bounds__(256) void gate_mfma_kernel(const T* __restrict__ X, const T* __restrict__ Wg,
+                                                        const float* __restrict__ bg, int N, int d, int E, int k,
+                                                        int32_t* __restrict__ topk_idx, float* __restrict__ topk_w)
+{
+    constexpr int KC = 32, V = 16 / sizeof(T), NPX = 8 / V;   // features per slab; 16-byte pieces per thread
+    constexpr int EB = 16 * NT;                               // experts per block (NT groups of 16)
+    __shared__ __align__(16) double smem[2 * KC * 64];      // sX [KC][64 tokens] | sW [KC][64 experts]; reused
+    double* sX = smem;
+    double* sW = smem + KC * 64;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long tok0 = (long)blockIdx.x * 64;
+    const double ninf = -__builtin_inf();
+    // staging roles: token features -> thread (token = tid % 64, 8-feature group = tid / 64)
+    const long trow = tok0 + lane < N ? tok0 + lane : (long)N - 1;
+    const T* xsrc = X + (size_t)trow * d + wave * 8;
+    // gate slab -> thread (feature = tid / 8, 8 experts from (tid % 8) * 8)
+    const int wf = threadIdx.x >> 3, we = (threadIdx.x & 7) * 8;
+
+    double v[kMaxK];
+    int id[kMaxK];
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j) { v[j] = ninf; id[j] = 0x7fffffff; }
+
+    for (int eb0 = 0; eb0 < E; eb0 += EB) {
+        f64x4 acc[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+        uint4 pre[NPX];
+#pragma unroll
+        for (int q = 0; q < NPX; ++q) pre[q] = reinterpret_cast<const uint4*>(xsrc)[q];
+        for (int c0 = 0; c0 < d; c0 += KC) {
+            __syncthreads();                                 // previous slab (or the logit patch) fully consumed
+            {
+                T tmp[8];
+#pragma unroll
+                for (int q = 0; q < NPX; ++q) reinterpret_cast<uint4*>(tmp)[q] = pre[q];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sX[(wave * 8 + u) * 64 + lane] = Elem<T>::get(tmp, u);
+                const T* wrow = Wg + (size_t)(c0 + wf) * E + eb0 + we;
+                if (we < EB) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        sW[wf * 64 + we + u] = eb0 + we + u < E ? Elem<T>::get(wrow, u) : 0.0;
+                }
+            }
+            if (c0 + KC < d) {
+#pragma unroll
+                for (int q = 0; q < NPX; ++q) pre[q] = reinterpret_cast<const uint4*>(xsrc + c0 + KC)[q];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < KC / 4; ++kk) {
+                const int row = (kk * 4 + (lane >> 4)) * 64 + (lane & 15);
+                const double a = sX[row + wave * 16];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, sW[row + nt * 16], acc[nt], 0, 0, 0);
+            }
+        }
+        __syncthreads();                                     // all waves are done with the slabs
+        double* sL = smem;                                   // [64 tokens][64 experts]
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                sL[(wave * 16 + 4 * r + (lane >> 4)) * 64 + nt * 16 + (lane & 15)] = acc[nt][r];
+        __syncthreads();
+        for (int e = 0; e < EB / 4; ++e) {                   // lane = token, this wavefront's quarter of the block
+            const int ge = eb0 + wave * (EB / 4) + e;
+            if (ge < E) {                                    // wave-uniform
+                double l = sL[lane * 64 + wave * (EB / 4) + e] + (bg ? (double)bg[ge] : 0.0);
+                if (!(l == l)) l = ninf;                     // NaN ranks last; indices stay in range
+                topk_insert(l, ge, v, id, k);
+            }
+        }
+    }
+    // merge the four per-wavefront lists
+    __syncthreads();
+    double* mV = smem;                                       // [wave][slot][token]
+    int* mI = reinterpret_cast<int*>(smem + 4 * kMaxK * 64);
+#pragma unroll
+    for (int j = 0; j < kMaxK; ++j)
+        if (j < k) {
+            mV[(wave * kMaxK + j) * 64 + lane] = v[j];
+            mI[(wave * kMaxK + j) * 64 + lane] = id[j];
+        }
+    __syncthreads();
+    if (wave == 0) {
+        for (int w = 1; w < 4; ++w)
+#pragma unroll
+            for (int j = 0; j < kMaxK; ++j)
+                if (j < k) topk_insert(mV[(w * kMaxK + j) * 64 + lane], mI[(w * kMaxK + j) * 64 + lane], v, id, k);
+        const long t = tok0 + lane;
+        if (t < N) {
+            double ex[kMaxK], den = 0.0;
+#pragma unroll
+            for (int j = 0; j < kMaxK; ++j)
+                if (j < k) {
+                    ex[j] = exp(v[j] - v[0]);
+                    den += ex[j];
+                }
+#pragma unroll
+            for (int j = 0; j < kMaxK; ++j)
+                if (j < k) {
+                    topk_idx[t * k + j] = id[j];
+                    topk_w[t * k + j] = (float)(ex[j] / den);
+                }
+        }
+    }
+}
+
+template <typename T>
+static void launch_mfma(const moe_desc_t& D, const T* X, const T* Wg, const float* bg, int32_t* idx, float* w, hipStream_t st)
+{
+    const dim3 grid((unsigned)((D.N + 63) / 64));
+    if (D.E <= 32)
+        hipLaunchKernelGGL((gate_mfma_kernel<T, 2>), grid, dim3(256), 0, st, X, Wg, bg, D.N, D.d, D.E, D.k, idx, w);
+    else
+        hipLaunchKernelGGL((gate_mfma_kernel<T, 4>), grid, dim3(256), 0, st, X, Wg, bg, D.N, D.d, D.E, D.k, idx, w);
 }
 
 void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
                       float* topk_w, hipStream_t st)
 {
-    if (D.dtype == MOE_BF16)
-        launch_typed<unsigned short>(D, (const unsigned short*)X, (const unsigned short*)Wg, bg, topk_idx, topk_w, st);
-    else
-        launch_typed<float>(D, (const float*)X, (const float*)Wg, bg, topk_idx, topk_w, st);
+    // Few experts: a group of lanes per token with the products on the vector ALU wastes nothing; from 17 experts
+    // on the fp64 matrix cores win (measured: E=16 33 vs 79 us, E=32 527 vs 231 us, E=256 610 vs 157 us).
+    const bool lanes_over_experts = D.E <= 16;
+    if (D.dtype == MOE_BF16) {
+        using T = unsigned short;
+        if (lanes_over_experts) launch_typed<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, st);
+        else launch_mfma<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, st);
+    } else {
+        using T = float;
+        if (lanes_over_experts) launch_typed<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, st);
+        else launch_mfma<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, st);
+    }
 }
 
 }  // namespace moe

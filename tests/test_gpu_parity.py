@@ -25,6 +25,7 @@ CASES = [
     Workload("wide_gate_bf16", 512, 64, 64, 130, 4, "bf16", 0.0, 16),
     Workload("single_token_bf16", 1, 64, 96, 3, 2, "bf16", 0.0, 17),
     Workload("top8_f32", 33, 32, 32, 9, 8, "f32", 0.0, 18),
+    Workload("gate_over_256_experts_bf16", 200, 64, 32, 300, 3, "bf16", 0.0, 19),
 ]
 
 
@@ -84,7 +85,7 @@ def _full_check(w, grad_dtype=None, few_rows_per_expert=False):
 
 @pytest.mark.parametrize("w", CASES, ids=lambda w: w.name)
 def test_layer_matches_oracle(w):
-    _full_check(w, few_rows_per_expert=(w.name == "empty_experts_bf16"))
+    _full_check(w, few_rows_per_expert=(w.name in ("empty_experts_bf16", "gate_over_256_experts_bf16")))
 
 
 def test_fp32_weight_gradients_for_bf16_activations():
