@@ -22,27 +22,17 @@ struct WsLayout {
     size_t tileP;     // [4][E+1] int32: prefix of ceil(counts/BM) for BM = 32,64,128,256
     size_t order;     // [E] int32: experts by descending count (ties: lower id first)
     size_t hist;      // [nb][E] int32: per plan-chunk histogram, then exclusive base inside the expert
-    size_t dwg_part;  // [E][S][d] float: partial sums of dWg
-    size_t dbg_part;  // [E][S] float
+    size_t dwg_part;  // [pieces][d] float: partial sums of dWg over pieces of 64 rows
+    size_t dbg_part;  // [pieces] float
     size_t WgT;       // [E][d] gate matrix transposed (written by the backward pass), element type = desc.dtype
     size_t zeros;     // 1 KB of zeros (written by the plan step): source of masked reduction rows
     size_t total;
     int nb;           // plan chunks = ceil(M / kPlanChunk)
-    int S;            // row splits per expert for the dWg reduction
+    long dwg_pieces;  // upper bound of 64-row pieces over all experts: floor(M/64) + E
 };
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t dtype_size(int dt) { return dt == MOE_BF16 ? 2 : 4; }
-
-inline int dwg_splits(const moe_desc_t& D)
-{
-    long M = (long)D.N * D.k;
-    long avg = D.E > 0 ? M / D.E : 0;
-    long s = (avg + 31) / 32;
-    if (s < 1) s = 1;
-    if (s > 32) s = 32;
-    return (int)s;
-}
 
 inline WsLayout ws_layout(const moe_desc_t& D)
 {
@@ -62,9 +52,9 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.order = take((size_t)D.E * sizeof(int32_t));
     L.nb = (int)((M + kPlanChunk - 1) / kPlanChunk);
     L.hist = take((size_t)(L.nb > 0 ? L.nb : 1) * D.E * sizeof(int32_t));
-    L.S = dwg_splits(D);
-    L.dwg_part = take((size_t)D.E * L.S * D.d * sizeof(float));
-    L.dbg_part = take((size_t)D.E * L.S * sizeof(float));
+    L.dwg_pieces = (long)(M / 64) + D.E;
+    L.dwg_part = take((size_t)L.dwg_pieces * D.d * sizeof(float));
+    L.dbg_part = take((size_t)L.dwg_pieces * sizeof(float));
     L.WgT = take((size_t)D.E * D.d * b);
     L.zeros = take(1024);
     L.total = o;

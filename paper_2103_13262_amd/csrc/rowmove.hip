@@ -170,50 +170,57 @@ __global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs,
 }
 
 // ---- dWg[:,e] = sum over rows r of segment e of dl[perm[r]] * Xs[r,:]  (fixed order) ----------
-// grid (E, S, ceil(cpr/128)); each thread owns one 16-byte column piece and walks its share of rows.
+// Every expert's segment is cut into pieces of 64 rows (the 64-row tile table of the plan step), so the
+// work per workgroup is the same however skewed the load is.  grid (max pieces, ceil(cpr/128)); each thread
+// owns one 16-byte column piece and walks the rows of its piece; a second kernel adds an expert's pieces
+// in ascending order.
 template <typename T>
 __global__ __launch_bounds__(128) void dwg_partial(const void* __restrict__ Xs, const float* __restrict__ dl,
                                                    const int32_t* __restrict__ perm, const int32_t* __restrict__ counts,
-                                                   const int32_t* __restrict__ offsets, float* __restrict__ part,
-                                                   float* __restrict__ bpart, int S, int d, int cpr)
+                                                   const int32_t* __restrict__ offsets, const int32_t* __restrict__ P64,
+                                                   float* __restrict__ part, float* __restrict__ bpart, int E, int d,
+                                                   int cpr)
 {
     constexpr int V = Vec<T>::N;
-    const int e = blockIdx.x, s = blockIdx.y;
-    const int c = blockIdx.z * 128 + threadIdx.x;
-    const int cnt = counts[e], off = offsets[e];
-    const int per = (cnt + S - 1) / S;
-    int lo = s * per;
-    int hi = lo + per < cnt ? lo + per : cnt;
-    if (lo > hi) lo = hi;
+    const int piece = blockIdx.x;
+    if (piece >= P64[E]) return;
+    int lo = 0, hi = E;                   // largest e with P64[e] <= piece
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (P64[mid] <= piece) lo = mid; else hi = mid;
+    }
+    const int e = lo;
+    const int r0 = offsets[e] + (piece - P64[e]) * 64;
+    const int r1 = min(r0 + 64, offsets[e] + counts[e]);
+    const int c = blockIdx.y * 128 + threadIdx.x;
+    if (c >= cpr) return;
     float acc[V], sdl = 0.f;
 #pragma unroll
     for (int u = 0; u < V; ++u) acc[u] = 0.f;
-    if (c < cpr) {
-        for (int r = off + lo; r < off + hi; ++r) {
-            const float g = dl[perm[r]];
-            float v[V];
-            Vec<T>::load(Xs, (size_t)r * cpr + c, v);
+    for (int r = r0; r < r1; ++r) {
+        const float g = dl[perm[r]];
+        float v[V];
+        Vec<T>::load(Xs, (size_t)r * cpr + c, v);
 #pragma unroll
-            for (int u = 0; u < V; ++u) acc[u] = fmaf(g, v[u], acc[u]);
-            sdl += g;
-        }
-        float* dst = part + ((size_t)e * S + s) * d + (size_t)c * V;
-#pragma unroll
-        for (int u = 0; u < V; ++u) dst[u] = acc[u];
-        if (c == 0) bpart[(size_t)e * S + s] = sdl;
+        for (int u = 0; u < V; ++u) acc[u] = fmaf(g, v[u], acc[u]);
+        sdl += g;
     }
+    float* dst = part + (size_t)piece * d + (size_t)c * V;
+#pragma unroll
+    for (int u = 0; u < V; ++u) dst[u] = acc[u];
+    if (c == 0) bpart[piece] = sdl;
 }
 
 template <typename G>
 __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part, const float* __restrict__ bpart,
-                                                 G* __restrict__ dWg, float* __restrict__ dbg, int S, int d, int E,
-                                                 int accumulate)
+                                                 const int32_t* __restrict__ P64, G* __restrict__ dWg,
+                                                 float* __restrict__ dbg, int d, int E, int accumulate)
 {
     const long i = (long)blockIdx.x * 256 + threadIdx.x;  // i = row * E + e of dWg
     if (i < (long)d * E) {
         const int row = (int)(i / E), e = (int)(i % E);
         float s = 0.f;
-        for (int q = 0; q < S; ++q) s += part[((size_t)e * S + q) * d + row];
+        for (int q = P64[e]; q < P64[e + 1]; ++q) s += part[(size_t)q * d + row];
         if constexpr (sizeof(G) == 2) {
             if (accumulate) s += bf16_to_f32(dWg[i]);
             dWg[i] = f32_to_bf16(s);
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part,
     }
     if (dbg && i < E) {
         float s = 0.f;
-        for (int q = 0; q < S; ++q) s += bpart[(size_t)i * S + q];
+        for (int q = P64[i]; q < P64[i + 1]; ++q) s += bpart[q];
         if (accumulate) s += dbg[i];
         dbg[i] = s;
     }
@@ -279,7 +286,8 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     const int cpr = (int)((size_t)D.d * dtype_size(D.dtype) / 16);
     float* part = (float*)(ws + L.dwg_part);
     float* bpart = (float*)(ws + L.dbg_part);
-    const dim3 pg(D.E, L.S, (cpr + 127) / 128);
+    const int32_t* P64 = (const int32_t*)(ws + L.tileP) + tile_height_index(64) * (D.E + 1);
+    const dim3 pg((unsigned)L.dwg_pieces, (cpr + 127) / 128);
     const unsigned fg = (unsigned)(((long)D.d * D.E + 255) / 256);
     const unsigned xg = grid_for((long)D.N * cpr);
     const unsigned tg = (unsigned)(((long)D.d * D.E + 255) / 256);
@@ -287,21 +295,21 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     if (D.dtype == MOE_BF16) {
         using T = unsigned short;
         hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
-        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, part, bpart, L.S, D.d, cpr);
+        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
         if (D.grad_dtype == MOE_BF16)
             hipLaunchKernelGGL(dwg_final<unsigned short>, dim3(fg), dim3(256), 0, st, (const float*)part,
-                               (const float*)bpart, (unsigned short*)dWg, dbg, L.S, D.d, D.E, D.accumulate);
+                               (const float*)bpart, P64, (unsigned short*)dWg, dbg, D.d, D.E, D.accumulate);
         else
             hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
-                               (float*)dWg, dbg, L.S, D.d, D.E, D.accumulate);
+                               P64, (float*)dWg, dbg, D.d, D.E, D.accumulate);
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
                            (long)D.N, D.k, cpr);
     } else {
         using T = float;
         hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
-        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, part, bpart, L.S, D.d, cpr);
+        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
         hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
-                           (float*)dWg, dbg, L.S, D.d, D.E, D.accumulate);
+                           P64, (float*)dWg, dbg, D.d, D.E, D.accumulate);
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
                            (long)D.N, D.k, cpr);
     }
