@@ -51,6 +51,13 @@ def cpu_baseline(w, inputs, n_tokens):
                       f"weight gradients, {dt:.1f} s"}
 
 
+# HBM bytes per grouped-GEMM launch (mean of the six launches of a step), from two rocprofv3 --pmc runs of this
+# file (FETCH_SIZE, then WRITE_SIZE), each divided by what the same counter reads for a plain 1 GiB copy
+# (0.500 and 1.000 of the true KiB); profiles/C1_hbm_traffic_pmc.md holds the commands and per-kernel figures.
+# Counters cannot be read from inside a run, so this is the stored measurement, not a live one.
+MEASURED_HBM_BYTES_PER_GEMM_LAUNCH = {"C1": 316.3e6}
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -123,9 +130,10 @@ def main():
     peak = PEAK_BF16_TFLOPS if bf else PEAK_FP32_TFLOPS
     for n, (c, t) in gemm.items():
         kern[n]["tflops"] = flops_launch / (t / c * 1e-3) / 1e12
-    roofline = {"bound": "mfma" if bf else "alu", "kernel": "ggemm_bf16_kernel (6 launches per step)" if bf
+    roofline = {"bound": "mfma" if bf else "alu", "kernel": "ggemm_dma_kernel (6 launches per step)" if bf
                 else "ggemm_f32_kernel (6 launches per step)",
-                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                "traffic": MEASURED_HBM_BYTES_PER_GEMM_LAUNCH.get(w.name) if not a.custom else None,
                 "flops_per_launch": flops_launch, "avg_launch_us": avg_launch_ms * 1e3}
 
     out = {
