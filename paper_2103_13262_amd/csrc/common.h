@@ -12,6 +12,8 @@ constexpr int kMaxE = 1024;
 constexpr int kMaxK = 8;
 constexpr int kPlanChunk = 1024;  // assignments ranked by one workgroup of the plan kernels
 constexpr int kNumTileHeights = 4;  // row-tile prefix tables are kept for 32, 64, 128, 256 rows
+constexpr int kMaxPersistentWgs = 256;               // persistent grouped-GEMM workgroups (one per compute unit)
+constexpr size_t kPartialBytesPerWg = 256 * 256 * 4;  // one fp32 output tile of partial sums per workgroup
 __host__ __device__ constexpr int tile_height(int q) { return 32 << q; }
 __host__ __device__ constexpr int tile_height_index(int bm) { return bm == 32 ? 0 : bm == 64 ? 1 : bm == 128 ? 2 : 3; }
 
@@ -26,11 +28,15 @@ struct WsLayout {
     size_t dbg_part;  // [pieces] float
     size_t WgT;       // [E][d] gate matrix transposed (written by the backward pass), element type = desc.dtype
     size_t zeros;     // 1 KB of zeros (written by the plan step): source of masked reduction rows
+    size_t sk_flags;  // [kMaxPersistentWgs] int32, directly behind the zero page and zeroed with it: "partial sum ready"
+    size_t sk_error;  // int32 behind the flags, zeroed with them: set if a wait for a partial sum ran out
+    size_t sk_part;   // [kMaxPersistentWgs] fp32 tiles: partial sums of split output tiles (bf16 only)
     size_t total;
     int nb;           // plan chunks = ceil(M / kPlanChunk)
     long dwg_pieces;  // upper bound of 64-row pieces over all experts: floor(M/64) + E
 };
 
+constexpr size_t kZeroedBytes = 1024 + kMaxPersistentWgs * sizeof(int32_t) + 256;  // zero page, flags, error word
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t dtype_size(int dt) { return dt == MOE_BF16 ? 2 : 4; }
 
@@ -56,7 +62,10 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.dwg_part = take((size_t)L.dwg_pieces * D.d * sizeof(float));
     L.dbg_part = take((size_t)L.dwg_pieces * sizeof(float));
     L.WgT = take((size_t)D.E * D.d * b);
-    L.zeros = take(1024);
+    L.zeros = take(kZeroedBytes);
+    L.sk_flags = L.zeros + 1024;
+    L.sk_error = L.sk_flags + kMaxPersistentWgs * sizeof(int32_t);
+    L.sk_part = take(D.dtype == MOE_BF16 ? kMaxPersistentWgs * kPartialBytesPerWg : 0);
     L.total = o;
     return L;
 }
@@ -107,14 +116,16 @@ struct GemmArgs {
     const int32_t* tileP;  // [4][E+1]
     const int32_t* order;  // [E]
     const void* zeros;     // 1 KB of zeros
+    void* sk_part;         // partial-sum tiles, one per persistent workgroup
+    int32_t* sk_flags;     // one flag per persistent workgroup, all zero between launches
+    int32_t* sk_error;
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT
-    int debug;        // development only: selects a tile configuration
-    long long* trace; // development only: per-workgroup phase timestamps (8 per workgroup) or NULL
+    long long* trace; // development builds only: per-workgroup phase times (8 words per workgroup) or NULL
 };
 void launch_ggemm_f32(const GemmArgs& a, hipStream_t st);
-void launch_ggemm_bf16(const GemmArgs& a, hipStream_t st);
 void launch_ggemm_bf16_dma(const GemmArgs& a, hipStream_t st);
+void launch_ggemm_bf16_sk(const GemmArgs& a, hipStream_t st);
 
 // ---- small device helpers ------------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }

@@ -487,7 +487,7 @@ void launch_cfg(const GemmArgs& a, hipStream_t st)
 
 template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
 {
-    switch (a.debug) {   // development switch between tile configurations
+    switch (0) {   // development switch between tile configurations
         case 1: launch_cfg<KIND, 2, 2, 4, 4, 2, 64>(a, st); break;   // 256x256, BK 64, 2 stages
         case 2: launch_cfg<KIND, 2, 2, 4, 2, 3, 64>(a, st); break;   // 256x128, BK 64, 3 stages
         case 3: launch_cfg<KIND, 2, 4, 4, 2, 4, 32>(a, st); break;   // 256x256, 8 waves, BK 32, 4 stages

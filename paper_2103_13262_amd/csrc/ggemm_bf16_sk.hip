@@ -1,0 +1,803 @@
+// Grouped bf16 matrix products on the matrix cores, persistent form.
+//
+// One workgroup per compute unit stays resident for the whole launch and walks a list of work items.
+// A work item is an output tile (BM x BN) together with a range of its reduction blocks (BK deep):
+//   * whole tiles, handed out in rounds (workgroup j of an XCD takes tile j, j + W, ... of the XCD's share), and
+//   * for the tiles left over after the last full round, equal pieces of their reduction ("stream-K"): the
+//     left-over tiles of an XCD are laid end to end, block by block, and cut into one contiguous range per
+//     workgroup.  A range that ends inside a tile yields a partial sum, written in fp32 to a per-workgroup
+//     buffer; a range that begins inside a tile first adds the partial sum of the workgroup before it (which
+//     holds the preceding blocks of that tile), so the sum runs along the tile's workgroups in ascending
+//     order (a fixed order: results do not depend on timing) and the workgroup whose range holds the tile's
+//     last block writes the tile.  Every workgroup handles the piece at the end of its range first, and a
+//     workgroup waits only for the one numbered just below it, so the waits cannot form a cycle.
+// Operands travel from global memory straight into an LDS ring (global_load_lds_dwordx4), the first blocks
+// of the next work item are requested before the epilogue of the current one, and the epilogue runs through
+// a small LDS patch of its own so that it does not disturb the ring.
+//
+// Workgroup: WM x WN wavefronts, each owning TM x TN accumulators of v_mfma_f32_32x32x16_bf16.
+//
+// LDS layouts of the ring (each wave-level load fills one contiguous 1 KB piece, lane p -> byte 16*p, so a
+// layout is chosen by choosing which global 16-byte chunk each lane fetches):
+//   k-contiguous source ([row][k]):  LDS row = 2*BK bytes; 16-byte chunk c of row r sits at position
+//       c ^ swz(r); operand reads are ds_read_b128 and free of bank conflicts.
+//   row-contiguous source ([k][row], the reduction index is the slow one: weights in the forward products,
+//       both operands of the weight gradients): LDS keeps the global layout, chunk c of k-row k at position
+//       c ^ 2*(k&3); operands are gathered with ds_read_b64_tr_b16.
+// Rows / columns outside a tile's valid extent are fetched from a clamped (valid) address and their results
+// are never stored.  Reduction indices past the end are fetched from a page of zeros.
+//
+// The Gaussian factors of GeLU and GeLU' are looked up at the bf16 value zb that is stored as the
+// pre-activation, so they are functions of 16 bits: an LDS table indexed by the bit pattern (built from erfc /
+// exp at launch) gives Phi(zb) resp. Phi(zb) + zb phi(zb) exactly for 2^-11 <= |zb| < 8 and the nearest table
+// entry outside (|error| < 4e-4).  Forward: H = z Phi(zb) with z the fp32 accumulator; rounding z inside Phi
+// changes H by at most z^2 phi(z) 2^-9 < 6e-4, a fraction of H's own bf16 rounding.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <type_traits>
+#include <utility>
+#include <vector>
+
+#include "common.h"
+
+namespace moe {
+namespace sk {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef unsigned short u16;
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr int kMinSplitBlocks = 4;              // a stream-K piece is at least this many reduction blocks
+constexpr int kActLo = (127 - 11) << 7;         // bf16 bit pattern of 2^-11
+constexpr int kActHi = (127 + 3) << 7;          // bf16 bit pattern of 2^3
+constexpr int kActEntries = kActHi - kActLo;    // table entries per sign
+constexpr int kSpinLimit = 1 << 20;             // bounded wait for a partial sum (on the order of a second)
+
+template <int BK> __device__ __forceinline__ int swz(int r)
+{
+    if constexpr (BK == 32) return ((r >> 1) & 3) ^ ((r >> 3) & 1);
+    else return (r >> 1) & 7;
+}
+
+// s_waitcnt vmcnt(N) only (export and LDS counters left at their maxima), gfx9 encoding.
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+template <int PER, int MAXG> __device__ __forceinline__ void wait_groups(int groups)
+{   // allow `groups` (0..MAXG) load groups of PER instructions each to stay in flight
+    if constexpr (MAXG == 0) { wait_vmcnt<0>(); }
+    else {
+        if (groups >= MAXG) wait_vmcnt<PER * MAXG>();
+        else wait_groups<PER, MAXG - 1>(groups);
+    }
+}
+
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK_>
+struct Cfg {
+    static constexpr int BK = BK_;
+    static constexpr int NW = WM * WN, NT = NW * 64;
+    static constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+    static constexpr bool A_TRANS = KIND == kColsT;
+    static constexpr bool B_TRANS = KIND == kRowsNN || KIND == kRowsNN_GeLU || KIND == kColsT;
+    static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LA = A_BYTES / 1024 / NW, LB = B_BYTES / 1024 / NW;   // wave-level loads per wave and stage
+    static constexpr int RING = STAGES * STAGE_BYTES;
+    static constexpr int PITCH = TN * 32 + 8;                 // floats per patch row: rows 4 apart are 32 banks apart
+    static constexpr int PATCH_BYTES = NW * 8 * PITCH * 4;    // 8 rows per wave
+    static constexpr bool TABLE = KIND == kRowsNN_GeLU || KIND == kRowsNT_dGeLU;
+    static constexpr int TABLE_BYTES = TABLE ? 2 * kActEntries * 4 : 0;
+    static constexpr int SMEM = RING + PATCH_BYTES + TABLE_BYTES;
+    static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile must split evenly over waves");
+    static_assert(SMEM <= 160 * 1024, "LDS budget");
+};
+
+// Entry i of the activation table: Phi(z) (forward) or Phi(z) + z phi(z) (backward) at the bf16 value whose
+// magnitude pattern is kActLo + i % kActEntries and whose sign is i / kActEntries.
+template <int KIND> __device__ __forceinline__ float act_entry(int i)
+{
+    const int s = i >= kActEntries ? 1 : 0;
+    const float z = bf16_to_f32((u16)((i - s * kActEntries + kActLo) | (s << 15)));
+    const float cdf = 0.5f * erfcf(-z * 0.70710678118654752f);
+    if constexpr (KIND == kRowsNN_GeLU) return cdf;
+    else return cdf + z * expf(-0.5f * z * z) * 0.39894228040143268f;
+}
+__device__ __forceinline__ int act_index(unsigned zb)   // zb: bf16 bit pattern in the low 16 bits
+{
+    int t = (int)(zb & 0x7fffu);
+    t = min(max(t, kActLo), kActHi - 1);
+    return t - kActLo + (int)((zb >> 15) & 1u) * kActEntries;
+}
+
+// Per-lane source pointers of one operand for reduction block 0 (advanced by the caller) and the
+// reduction offset inside a block that the lane's chunk starts at (krow).
+//   !TRANS: src[row][k]; one load covers 64 / (BK/8) rows.
+//    TRANS: src[k][row]; CPR = R/8 chunks per k-row; lane p of load j covers k-row j*(64/CPR) + p/CPR.
+template <bool TRANS, int R, int NW, int L, int BK>
+__device__ __forceinline__ void setup_ptrs(const u16* base, long ld, int valid, int wave, int lane, const u16* (&ptr)[L],
+                                           int (&krow)[L])
+{
+#pragma unroll
+    for (int i = 0; i < L; ++i) {
+        const int j = wave + i * NW;
+        if constexpr (!TRANS) {
+            constexpr int CK = BK / 8;
+            int row = j * (64 / CK) + lane / CK;
+            const int c = (lane % CK) ^ swz<BK>(row);
+            row = row < valid ? row : valid - 1;
+            ptr[i] = base + (long)row * ld + c * 8;
+            krow[i] = c * 8;
+        } else {
+            constexpr int CPR = R / 8;
+            const int kr = j * (64 / CPR) + lane / CPR;
+            int c = (lane % CPR) ^ (2 * (kr & 3));
+            c = c * 8 < valid ? c : 0;
+            ptr[i] = base + (long)kr * ld + c * 8;
+            krow[i] = kr;
+        }
+    }
+}
+
+// One work item (all fields are uniform over the workgroup).
+struct Item {
+    const u16* A; long lda;
+    const u16* B; long ldb;
+    size_t c_off;
+    int Mt, Nt, Kt;       // valid rows / columns of the tile, reduction length
+    int kb0, kb1;         // reduction blocks [kb0, kb1) of the tile
+    int owner;            // the range holds the tile's last block: this workgroup writes the tile
+};
+
+struct Fin {              // what finishing an item needs once the streams have moved on to the next one
+    size_t c_off;
+    int Mt, Nt, owner;
+};
+
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
+__global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, int ntm, int ntn)
+{
+    using C = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
+    constexpr int BM = C::BM, BN = C::BN, NT = C::NT, PITCH = C::PITCH;
+    extern __shared__ __align__(1024) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+#ifdef MOE355_DEV_TRACE
+    long long tr[4] = {0, 0, 0, 0}, t_mark = wall_clock64(), t_begin = t_mark;
+    int tr_items = 0;
+#define TRACE_PHASE(i) { const long long now = wall_clock64(); tr[i] += now - t_mark; t_mark = now; }
+#else
+#define TRACE_PHASE(i)
+#endif
+
+    float* patch = (float*)(smem + C::RING) + wave * (8 * PITCH);
+    const float* act = (const float*)(smem + C::RING + C::PATCH_BYTES);
+    if constexpr (C::TABLE) {   // visible to all waves after the first barrier, long before the first epilogue
+        float* w = (float*)(smem + C::RING + C::PATCH_BYTES);
+        for (int i = tid; i < 2 * kActEntries; i += NT) w[i] = act_entry<KIND>(i);
+    }
+
+    // ---------------- schedule of this workgroup ----------------
+    const int xcd = blockIdx.x & 7, wj = blockIdx.x >> 3, W = gridDim.x >> 3;
+    const int32_t* P = g.tileP + tile_height_index(BM) * (g.E + 1);
+    long start = 0, n_dp = 0;        // rows kinds: first tile of this XCD's share; number of whole-tile items
+    int rem = 0, S = 0, Wp = 0;      // stream-K: left-over tiles, their blocks, participating workgroups
+    int nkT = 0;                     // rows kinds: reduction blocks per tile
+    int sk_a = 0, sk_cur = 0;        // stream-K blocks of this workgroup not yet done: [sk_a, sk_cur)
+    long dp_i, dp_stride;            // next whole-tile item and the stride to the one after
+    int tpe = 0, per = 0;            // weight gradients: tiles per expert, and per expert and XCD
+    if constexpr (KIND != kColsT) {
+        const long T = (long)P[g.E] * ntn;
+        const long base = T >> 3;
+        const int extra = (int)(T & 7);
+        const long n_x = base + (xcd < extra ? 1 : 0);
+        start = xcd * base + min(xcd, extra);
+        nkT = (g.K + BK - 1) / BK;
+        rem = (int)(n_x % W);
+        if (rem * 10 >= W * 9) rem = 0;       // a nearly full last round is not worth splitting
+        n_dp = n_x - rem;
+        S = rem * nkT;
+        Wp = rem ? min(W, max(1, S / kMinSplitBlocks)) : 0;
+        if (wj < Wp) { sk_a = (int)((long)wj * S / Wp); sk_cur = (int)((long)(wj + 1) * S / Wp); }
+        dp_i = wj; dp_stride = W;
+    } else {
+        tpe = ntm * ntn;
+        if ((tpe & 7) == 0) { per = tpe >> 3; n_dp = (long)g.E * per; dp_i = wj; dp_stride = W; }
+        else { n_dp = (long)g.E * tpe; dp_i = blockIdx.x; dp_stride = gridDim.x; }
+    }
+
+    auto decode_rows = [&](long L, Item& it) {
+        int lo = 0, hi = g.E;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if ((long)P[mid] * ntn <= L) lo = mid; else hi = mid;
+        }
+        const int e = lo;
+        const int mte = P[e + 1] - P[e];
+        const int local = (int)(L - (long)P[e] * ntn);
+        // Order inside an expert: groups of up to GM row blocks; inside a group the row block runs fastest,
+        // then the column block, so that tiles that run at the same time on one XCD share operand panels.
+        constexpr int GM = 8;
+        int nt, mt;
+        {
+            const int full = mte / GM, per_group = GM * ntn;
+            const int gi = local / per_group;
+            if (gi < full) {
+                const int r = local - gi * per_group;
+                nt = r / GM;
+                mt = gi * GM + (r - nt * GM);
+            } else {
+                const int remm = mte - full * GM;
+                const int r = local - full * per_group;
+                nt = r / remm;
+                mt = full * GM + (r - nt * remm);
+            }
+        }
+        const long r0 = (long)g.offsets[e] + (long)mt * BM;
+        const int n0 = nt * BN;
+        it.A = (const u16*)g.A + r0 * g.K;  it.lda = g.K;
+        const u16* Be = (const u16*)g.B + (size_t)e * g.K * g.Nout;
+        if constexpr (C::B_TRANS) { it.B = Be + n0; it.ldb = g.Nout; }
+        else                      { it.B = Be + (size_t)n0 * g.K; it.ldb = g.K; }
+        it.c_off = (size_t)r0 * g.Nout + n0;
+        it.Mt = min(BM, g.counts[e] - mt * BM);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.K;
+    };
+    auto next_item = [&](Item& it) -> bool {
+        if constexpr (KIND != kColsT) {
+            if (sk_cur > sk_a) {       // stream-K pieces, last one first
+                const int tt = (sk_cur - 1) / nkT;
+                const int seg0 = max(sk_a, tt * nkT);
+                it.kb0 = seg0 - tt * nkT;  it.kb1 = sk_cur - tt * nkT;
+                it.owner = it.kb1 == nkT;
+                sk_cur = seg0;
+                decode_rows(start + tt, it);
+                return true;
+            }
+            if (dp_i < n_dp) {
+                decode_rows(start + rem + dp_i, it);
+                dp_i += dp_stride;
+                it.kb0 = 0;  it.kb1 = nkT;  it.owner = 1;
+                return true;
+            }
+            return false;
+        } else {
+            if (dp_i >= n_dp) return false;
+            int ord, q;
+            if (per) { ord = (int)(dp_i / per); q = xcd * per + (int)(dp_i - (long)ord * per); }
+            else     { ord = (int)(dp_i / tpe); q = (int)(dp_i - (long)ord * tpe); }
+            dp_i += dp_stride;
+            const int e = g.order[ord];
+            const int m0 = (q / ntn) * BM, n0 = (q % ntn) * BN;
+            const long off = g.offsets[e];
+            it.A = (const u16*)g.A + off * g.K + m0;     it.lda = g.K;
+            it.B = (const u16*)g.B + off * g.Nout + n0;  it.ldb = g.Nout;
+            it.c_off = ((size_t)e * g.K + m0) * g.Nout + n0;
+            it.Mt = min(BM, g.K - m0);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.counts[e];
+            it.kb0 = 0;  it.kb1 = (it.Kt + BK - 1) / BK;  it.owner = 1;
+            return true;
+        }
+    };
+
+    // ---------------- global -> LDS streams ----------------
+    const u16* pa[C::LA]; int ka[C::LA];
+    const u16* pb[C::LB]; int kb[C::LB];
+    long stepA = 0, stepB = 0;
+    int Kt = 0, kb0 = 0;                     // of the item whose loads are being issued
+    const u16* zeros = (const u16*)g.zeros + lane * 8;
+    // reduction indices past Kt are read from the zero page: always possible for the weight gradients (Kt = rows
+    // of the expert), and for the other kinds only when a block is deeper than the 32 that divides every width
+    constexpr bool KMASK = KIND == kColsT || BK > 32;
+    // The loads are written as inline assembly so that the compiler does not serialise them against the LDS
+    // reads of other ring slots; the ordering is enforced by the explicit vmcnt waits and barriers below.
+    const unsigned lds_base = (unsigned)(uintptr_t)LDS_PTR(char, smem);
+    // One wave-level load (index l of the LA + LB loads this wave owns per block) of the item's block number
+    // li (counted from kb0) into ring slot li % STAGES.  l is a compile-time constant at every call site.
+    auto issue_one = [&](int li, auto lc) {
+        constexpr int l = decltype(lc)::value;
+        const unsigned sA = lds_base + (li % STAGES) * C::STAGE_BYTES + wave * 1024;
+        if constexpr (l < C::LA) {
+            const u16* src = pa[l];
+            if constexpr (KMASK) src = ((kb0 + li) * BK + ka[l] < Kt) ? src : zeros;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(sA + l * C::NW * 1024), "v"(src) : "memory");
+            pa[l] += stepA;
+        } else {
+            constexpr int i = l - C::LA;
+            const u16* src = pb[i];
+            if constexpr (KMASK) src = ((kb0 + li) * BK + kb[i] < Kt) ? src : zeros;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(sA + C::A_BYTES + i * C::NW * 1024), "v"(src) : "memory");
+            pb[i] += stepB;
+        }
+    };
+    auto issue = [&](int li) {   // all loads of one block at once
+        [&]<int... L>(std::integer_sequence<int, L...>) {
+            (issue_one(li, std::integral_constant<int, L>{}), ...);
+        }(std::make_integer_sequence<int, C::LA + C::LB>{});
+    };
+    // Point the streams at an item and request its first blocks (the ring must be free).
+    auto start_item = [&](const Item& it) {
+        setup_ptrs<C::A_TRANS, BM, C::NW, C::LA, BK>(it.A, it.lda, it.Mt, wave, lane, pa, ka);
+        setup_ptrs<C::B_TRANS, BN, C::NW, C::LB, BK>(it.B, it.ldb, it.Nt, wave, lane, pb, kb);
+        stepA = C::A_TRANS ? (long)BK * it.lda : BK;
+        stepB = C::B_TRANS ? (long)BK * it.ldb : BK;
+#pragma unroll
+        for (int l = 0; l < C::LA; ++l) pa[l] += stepA * it.kb0;
+#pragma unroll
+        for (int l = 0; l < C::LB; ++l) pb[l] += stepB * it.kb0;
+        Kt = it.Kt;  kb0 = it.kb0;
+        const int nk = it.kb1 - it.kb0;
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s)
+            if (s < nk) issue(s);
+    };
+
+    // ---------------- per-lane LDS offsets of the MFMA operand fetches ----------------
+    int offA[TM], offB[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int rb = (wm * TM + i) * 32;
+        if constexpr (!C::A_TRANS) {
+            offA[i] = (rb + (lane & 31)) * (BK * 2) + ((((lane >> 5)) ^ swz<BK>(lane & 31)) << 4);
+        } else {
+            const int s = lane & 15, col = rb + ((lane >> 4) & 1) * 16 + 4 * (s & 3);
+            offA[i] = ((lane >> 5) * 8 + (s >> 2)) * (BM * 2) + ((((col >> 3)) ^ (2 * (s >> 2))) << 4) + (col & 7) * 2;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int rb = (wn * TN + j) * 32;
+        if constexpr (!C::B_TRANS) {
+            offB[j] = (rb + (lane & 31)) * (BK * 2) + ((((lane >> 5)) ^ swz<BK>(lane & 31)) << 4);
+        } else {
+            const int s = lane & 15, col = rb + ((lane >> 4) & 1) * 16 + 4 * (s & 3);
+            offB[j] = ((lane >> 5) * 8 + (s >> 2)) * (BN * 2) + ((((col >> 3)) ^ (2 * (s >> 2))) << 4) + (col & 7) * 2;
+        }
+    }
+    auto fetchA = [&](const char* tile, int i, int ks) -> bf16x8 {
+        if constexpr (!C::A_TRANS) {
+            return *(const bf16x8*)(tile + (offA[i] ^ (ks << 5)));
+        } else {
+            const char* p = tile + offA[i] + ks * 16 * (BM * 2);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p + 4 * (BM * 2)));
+            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, v);
+        }
+    };
+    auto fetchB = [&](const char* tile, int j, int ks) -> bf16x8 {
+        if constexpr (!C::B_TRANS) {
+            return *(const bf16x8*)(tile + (offB[j] ^ (ks << 5)));
+        } else {
+            const char* p = tile + offB[j] + ks * 16 * (BN * 2);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, p + 4 * (BN * 2)));
+            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, v);
+        }
+    };
+
+    f32x16 acc[TM][TN];
+    int tm_act = TM;   // 32-row blocks of this wave that hold at least one valid row of the current item
+
+    // Software pipeline over the nk blocks of the current item (its first min(nk, STAGES) blocks have been
+    // requested).  Ring slot li % STAGES holds block li.  The operand registers are double-buffered: while the
+    // matrix cores work on one 16-deep step, the LDS reads of the next step (which may belong to the next
+    // block) are in flight.  Per block there is one barrier, placed after this wave's last LDS read of the
+    // block, so that the slot can be refilled right behind it.
+    auto main_loop = [&](auto full_tag, const int nk) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        constexpr int PER = C::LA + C::LB;
+        static_assert((BK / 16) % 2 == 0, "even number of MFMA steps per block");
+        constexpr int KS = BK / 16;
+        bf16x8 fa[2][TM], fb[2][TN];
+        auto fetch = [&](int slot, int ks, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
+            const char* tA = smem + slot * C::STAGE_BYTES;
+            const char* tB = tA + C::A_BYTES;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = fetchB(tB, j, ks);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                if (FULL || i < tm_act) a[i] = fetchA(tA, i, ks);
+        };
+        // One 16-deep MFMA step.  The loads of the block that refills the slot freed at the last barrier are
+        // spread over the KS steps that follow that barrier, one place before each accumulator row.
+        constexpr int SLOTS = KS * TM;
+        auto mma = [&](const bf16x8 (&a)[TM], const bf16x8 (&b)[TN], auto step_c, int load_li) {
+            constexpr int STEP = decltype(step_c)::value;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                if (load_li >= 0) {
+                    [&]<int... L>(std::integer_sequence<int, L...>) {
+                        ((L * SLOTS / PER == STEP * TM + i ? (issue_one(load_li, std::integral_constant<int, L>{}), 0) : 0), ...);
+                    }(std::make_integer_sequence<int, PER>{});
+                }
+                if (FULL || i < tm_act) {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                }
+            }
+        };
+        fetch(0, 0, fa[0], fb[0]);
+        int load_li = -1;
+        auto steps_before_barrier = [&](int slot) {
+            [&]<int... S>(std::integer_sequence<int, S...>) {
+                ((fetch(slot, S + 1, fa[(S + 1) & 1], fb[(S + 1) & 1]),
+                  mma(fa[S & 1], fb[S & 1], std::integral_constant<int, S + 1>{}, load_li)), ...);
+            }(std::make_integer_sequence<int, KS - 1>{});
+        };
+        for (int li = 0; li + 1 < nk; ++li) {
+            steps_before_barrier(li % STAGES);
+            // own loads of block li+1 have landed (later blocks may stay in flight) and own LDS reads of
+            // block li are complete; after the barrier that holds for every wave
+            wait_groups<PER, STAGES - 2>(min(nk - 2 - li, STAGES - 2));
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), other counters untouched
+            __builtin_amdgcn_s_barrier();
+            load_li = li + STAGES < nk ? li + STAGES : -1;
+            fetch((li + 1) % STAGES, 0, fa[0], fb[0]);
+            mma(fa[1], fb[1], std::integral_constant<int, 0>{}, load_li);
+        }
+        steps_before_barrier((nk - 1) % STAGES);   // last block: nothing left to prefetch
+        mma(fa[1], fb[1], std::integral_constant<int, 0>{}, -1);
+    };
+
+    // ---------------- finishing a work item ----------------
+    // Partial sums of a split tile are exchanged through one fp32 buffer per workgroup, in the register layout
+    // of the accumulators (thread-major, 16 bytes per thread and accumulator quarter), so a wave-level access is
+    // one contiguous kilobyte.  They and the flags are written and read with agent-scope accesses (sc1): these
+    // are served where the XCDs' caches meet, so no cache needs to be written back or invalidated, and a store
+    // has reached that point when the wave's memory counter has drained.  The reading side lands the buffer in
+    // the (idle) LDS ring, many requests in flight at once, and adds it to its accumulators from there.
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    constexpr int PART_ROWS = TM * TN * 4;                       // 16-byte pieces per thread
+    constexpr int PART_ROW_BYTES = NT * 16;                      // one piece of every thread
+    constexpr int RING_ROWS = C::RING / PART_ROW_BYTES;          // pieces per thread that fit in the ring
+    static_assert(RING_ROWS >= 1, "ring too small to land partial sums");
+    auto store_partial = [&]() {
+        int tid_ = tid;
+        asm volatile("" : "+v"(tid_));   // keeps the address arithmetic of this cold path out of the main loop's registers
+        char* const dst = (char*)g.sk_part + (size_t)blockIdx.x * kPartialBytesPerWg + tid_ * 16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    // (the wait states keep the next instruction from overwriting the data registers of a store that
+                    // is wider than 64 bits while it still reads them: the compiler inserts them for its own stores
+                    // but cannot see into an assembly statement)
+                    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 2"
+                                 :: "v"(dst + ((i * TN + j) * 4 + q) * PART_ROW_BYTES), "v"(v) : "memory");
+                }
+        wait_vmcnt<0>();                       // this wave's partial sums have arrived ...
+        __syncthreads();                       // ... and so have those of the other waves
+        if (tid == 0) __hip_atomic_store(g.sk_flags + blockIdx.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    // Adds the partial sum of the workgroup just below (same XCD slot, one position lower).  The ring must be idle.
+    auto add_predecessor = [&]() {
+        const int id = blockIdx.x - 8;
+        if (tid == 0) {
+            int spins = 0;
+            while (__hip_atomic_load(g.sk_flags + id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 1) {
+                if (++spins > kSpinLimit) {   // cannot happen (see the header); kept so that every wave ends
+                    __hip_atomic_store(g.sk_error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(16);
+            }
+            __hip_atomic_store(g.sk_flags + id, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // as the next launch expects
+        }
+        __syncthreads();
+        int tid_ = tid;
+        asm volatile("" : "+v"(tid_));
+        const char* const src = (const char*)g.sk_part + (size_t)id * kPartialBytesPerWg + tid_ * 16;
+        const char* const mine = smem + tid_ * 16;   // every thread reads back exactly what its own wave requested
+#pragma unroll
+        for (int r0 = 0; r0 < PART_ROWS; r0 += RING_ROWS) {
+            // (the waits of this routine are assembly statements with a memory clobber: the compiler must not move
+            // the LDS reads across them, which it may do with the plain wait builtin)
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // LDS reads of the previous round are complete
+#pragma unroll
+            for (int r = r0; r < r0 + RING_ROWS && r < PART_ROWS; ++r)
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off sc1"
+                             :: "s"(lds_base + (r - r0) * PART_ROW_BYTES + wave * 1024), "v"(src + r * PART_ROW_BYTES) : "memory");
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int r = r0; r < r0 + RING_ROWS && r < PART_ROWS; ++r) {
+                const float4 pz = *(const float4*)(mine + (r - r0) * PART_ROW_BYTES);
+                const int i = r / (TN * 4), j = (r / 4) % TN, q = r % 4;
+                acc[i][j][4 * q] += pz.x;  acc[i][j][4 * q + 1] += pz.y;
+                acc[i][j][4 * q + 2] += pz.z;  acc[i][j][4 * q + 3] += pz.w;
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();              // every wave is done with the ring: the next item's blocks may land
+    };
+    auto pack8 = [](const float* f) {
+        return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                          pack_bf16x2(f[6], f[7]));
+    };
+    auto unpack8 = [](const uint4 u, float* f) {
+        const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            f[2 * t] = __uint_as_float(w[t] << 16);
+            f[2 * t + 1] = __uint_as_float(w[t] & 0xffff0000u);
+        }
+    };
+    // Accumulator element v of lane l is row (v/4)*8 + (l/32)*4 + v%4, column l%32 of its 32x32 block: the
+    // elements v = 4s .. 4s+3 of a wave's TN blocks form an 8-row slab.  Each wave passes one slab at a time
+    // through its private fp32 LDS patch and reads it back row-wise, 8 consecutive columns per lane, so that
+    // global memory sees 16-byte pieces of whole rows.  The LDS unit serves a wave's requests in order, so the
+    // next slab may be written into the patch as soon as the reads of the current one have been issued; the
+    // loop below keeps the patch traffic of slab s+1 and the table look-ups of slab s-1 in flight while the
+    // values of slab s are converted and stored.
+    constexpr int CPRW = TN * 4;                 // 8-column pieces per row of the wave tile
+    static_assert(8 * CPRW <= 64 || (8 * CPRW) % 64 == 0, "pieces per slab");
+    constexpr int PASSES = (8 * CPRW + 63) / 64;
+    auto epilogue = [&](const Fin& it) {
+        constexpr bool LOOKUP = C::TABLE;
+        const int ldc = g.Nout;
+        int lane_ = lane;
+        asm volatile("" : "+v"(lane_));   // keeps the address arithmetic of the epilogue out of the main loop's registers
+        float* const patch_w = patch + ((lane_ >> 5) * 4) * PITCH + (lane_ & 31);
+        const float* patch_r[PASSES]; int prow[PASSES], pcol[PASSES]; bool pok[PASSES];
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int q = lane_ + p * 64;
+            prow[p] = q / CPRW;
+            pcol[p] = wn * TN * 32 + (q % CPRW) * 8;
+            pok[p] = q < 8 * CPRW && pcol[p] < it.Nt;
+            patch_r[p] = patch + prow[p] * PITCH + (q % CPRW) * 8;
+        }
+        struct Slab { float4 lo[PASSES], hi[PASSES]; };
+        auto to_patch = [&](int i, int sl) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) patch_w[r * PITCH + j * 32] = acc[i][j][4 * sl + r];
+        };
+        auto from_patch = [&](Slab& v) {
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                v.lo[p] = *(const float4*)patch_r[p];
+                v.hi[p] = *(const float4*)(patch_r[p] + 4);
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (i >= tm_act) break;
+            const int row0 = (wm * TM + i) * 32;
+            uint4 zin[4][PASSES];
+            if constexpr (KIND == kRowsNT_dGeLU) {   // saved pre-activations of the whole block, requested up front
+#pragma unroll
+                for (int sl = 0; sl < 4; ++sl)
+#pragma unroll
+                    for (int p = 0; p < PASSES; ++p) {
+                        const int row = row0 + sl * 8 + prow[p];
+                        zin[sl][p] = make_uint4(0, 0, 0, 0);
+                        if (pok[p] && row < it.Mt)
+                            zin[sl][p] = *(const uint4*)((const u16*)g.Zin + it.c_off + (size_t)row * ldc + pcol[p]);
+                    }
+            }
+            Slab cur, nxt;
+            float xs[PASSES][8], fac[PASSES][8];   // values and looked-up factors of the slab before the current one
+            to_patch(i, 0);
+            from_patch(cur);
+#pragma unroll
+            for (int sl = 0; sl <= 4; ++sl) {
+                if (sl + 1 < 4) { to_patch(i, sl + 1); from_patch(nxt); }
+                if constexpr (LOOKUP) {
+                    if (sl > 0) {   // second half of slab sl-1: its factors have arrived
+#pragma unroll
+                        for (int p = 0; p < PASSES; ++p) {
+                            const int row = row0 + (sl - 1) * 8 + prow[p];
+                            if (!pok[p] || row >= it.Mt) continue;
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) xs[p][t] *= fac[p][t];
+                            const size_t o = it.c_off + (size_t)row * ldc + pcol[p];
+                            *(uint4*)((u16*)(KIND == kRowsNN_GeLU ? g.C2 : g.C) + o) = pack8(xs[p]);
+                        }
+                    }
+                }
+                if (sl == 4) break;
+#pragma unroll
+                for (int p = 0; p < PASSES; ++p) {
+                    const int row = row0 + sl * 8 + prow[p];
+                    if (!pok[p] || row >= it.Mt) continue;
+                    float x[8] = {cur.lo[p].x, cur.lo[p].y, cur.lo[p].z, cur.lo[p].w,
+                                  cur.hi[p].x, cur.hi[p].y, cur.hi[p].z, cur.hi[p].w};
+                    const size_t o = it.c_off + (size_t)row * ldc + pcol[p];
+                    if constexpr (KIND == kRowsNN_GeLU) {
+                        const uint4 zp = pack8(x);
+                        *(uint4*)((u16*)g.C + o) = zp;
+                        const unsigned w[4] = {zp.x, zp.y, zp.z, zp.w};
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {   // H = z Phi(zb): z in fp32, Phi looked up at its bf16 rounding zb
+                            fac[p][2 * t] = act[act_index(w[t])];
+                            fac[p][2 * t + 1] = act[act_index(w[t] >> 16)];
+                        }
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) xs[p][t] = x[t];
+                    } else if constexpr (KIND == kRowsNT_dGeLU) {
+                        const unsigned w[4] = {zin[sl][p].x, zin[sl][p].y, zin[sl][p].z, zin[sl][p].w};
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            fac[p][2 * t] = act[act_index(w[t])];
+                            fac[p][2 * t + 1] = act[act_index(w[t] >> 16)];
+                        }
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) xs[p][t] = x[t];
+                    } else if constexpr (KIND == kColsT) {
+                        if (g.out_f32) {
+                            float4* Cf = (float4*)((float*)g.C + o);
+                            if (g.accumulate) {
+                                const float4 p0 = Cf[0], p1 = Cf[1];
+                                x[0] += p0.x; x[1] += p0.y; x[2] += p0.z; x[3] += p0.w;
+                                x[4] += p1.x; x[5] += p1.y; x[6] += p1.z; x[7] += p1.w;
+                            }
+                            Cf[0] = make_float4(x[0], x[1], x[2], x[3]);
+                            Cf[1] = make_float4(x[4], x[5], x[6], x[7]);
+                        } else {
+                            uint4* Ch = (uint4*)((u16*)g.C + o);
+                            if (g.accumulate) {
+                                float prev[8];
+                                unpack8(*Ch, prev);
+#pragma unroll
+                                for (int t = 0; t < 8; ++t) x[t] += prev[t];
+                            }
+                            *Ch = pack8(x);
+                        }
+                    } else {
+                        *(uint4*)((u16*)g.C + o) = pack8(x);
+                    }
+                }
+                cur = nxt;
+            }
+        }
+    };
+
+    // ---------------- the work loop ----------------
+    Item cur;
+    bool have = next_item(cur);
+    if (have) start_item(cur);
+    TRACE_PHASE(0);
+    while (have) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        tm_act = (cur.Mt - wm * TM * 32 + 31) / 32;
+        tm_act = tm_act < 0 ? 0 : (tm_act > TM ? TM : tm_act);
+        const int nk = cur.kb1 - cur.kb0;
+        if (nk > 0) {
+            // The first blocks of this item were requested before the previous epilogue, whose own memory
+            // operations came later: wait for everything, then every wave may read ring slot 0.
+            wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            TRACE_PHASE(1);
+            if (tm_act == TM) main_loop(std::true_type{}, nk);
+            else main_loop(std::false_type{}, nk);   // tail tiles skip the 32-row blocks that hold no valid row
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_s_barrier();              // every wave is done reading the ring
+        }
+        TRACE_PHASE(2);
+        const Fin fin{cur.c_off, cur.Mt, cur.Nt, cur.owner};
+        if (cur.kb0 > 0) add_predecessor();   // the blocks before kb0 were summed by the workgroup just below
+        have = next_item(cur);
+        if (have) start_item(cur);
+        if (fin.owner) epilogue(fin);
+        else store_partial();
+        TRACE_PHASE(3);
+#ifdef MOE355_DEV_TRACE
+        ++tr_items;
+#endif
+    }
+#ifdef MOE355_DEV_TRACE
+    if (g.trace && tid == 0) {
+        long long* t = g.trace + (size_t)blockIdx.x * 8;
+        t[0] = tr[0]; t[1] = tr[1]; t[2] = tr[2]; t[3] = tr[3]; t[4] = tr_items; t[5] = t_begin; t[6] = wall_clock64(); t[7] = 1;
+    }
+#endif
+}
+
+// Persistent workgroups of one launch: one per compute unit, a multiple of the 8 XCDs, at most kMaxPersistentWgs
+// (the workspace holds one partial-sum buffer per workgroup).
+static int persistent_wgs()
+{
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cus = cus / 8 * 8;
+        return cus > kMaxPersistentWgs ? kMaxPersistentWgs : cus;
+    }();
+    return n;
+}
+
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
+void launch_cfg(const GemmArgs& a, hipStream_t st)
+{
+    using C = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
+    static_assert((size_t)C::BM * C::BN * 4 <= kPartialBytesPerWg, "partial-sum buffer");
+    auto kern = ggemm_sk_kernel<KIND, WM, WN, TM, TN, STAGES, BK>;
+    static bool attr_set = false;   // the LDS ring is larger than the default dynamic limit
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM) != hipSuccess)
+            return;   // launch skipped; the caller's hipGetLastError() reports the failure
+        attr_set = true;
+    }
+    const int wgs = persistent_wgs();
+    if (wgs < 8) { set_error("grouped GEMM: no device with at least 8 compute units"); return; }
+    const int ntn = (a.Nout + C::BN - 1) / C::BN;
+    const int ntm = KIND == kColsT ? (a.K + C::BM - 1) / C::BM : 0;
+    GemmArgs b = a;
+#ifdef MOE355_DEV_TRACE
+    static long long* buf = nullptr;
+    if (!buf) (void)hipMalloc(&buf, 8 * sizeof(long long) * kMaxPersistentWgs);
+    b.trace = buf;
+    (void)hipMemsetAsync(buf, 0, 8 * sizeof(long long) * wgs, st);
+#endif
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(C::NT), C::SMEM, st, b, ntm, ntn);
+#ifdef MOE355_DEV_TRACE
+    {
+        std::vector<long long> h(8 * wgs);
+        (void)hipStreamSynchronize(st);
+        (void)hipMemcpy(h.data(), b.trace, h.size() * sizeof(long long), hipMemcpyDeviceToHost);
+        double ph[4] = {0, 0, 0, 0}, items = 0; long long tmin = 0, tmax = 0, emin = 0; int n = 0;
+        for (int i = 0; i < wgs; ++i) {
+            const long long* t = &h[8 * i];
+            if (!t[7]) continue;
+            if (!n || t[5] < tmin) tmin = t[5];
+            if (!n || t[6] > tmax) tmax = t[6];
+            if (!n || t[6] < emin) emin = t[6];
+            ++n;
+            for (int k = 0; k < 4; ++k) ph[k] += (double)t[k];
+            items += (double)t[4];
+        }
+        {   // the three workgroups that end last, and the one that ends first
+            std::vector<int> idx;
+            for (int i = 0; i < wgs; ++i) if (h[8 * i + 7]) idx.push_back(i);
+            std::sort(idx.begin(), idx.end(), [&](int a, int b) { return h[8 * a + 6] > h[8 * b + 6]; });
+            for (size_t k = 0; k < idx.size(); ++k) {
+                if (k >= 3 && k + 1 != idx.size()) continue;
+                const long long* t = &h[8 * idx[k]];
+                fprintf(stderr, "    wg %3d (xcd %d pos %2d) end %.1f us: items %lld setup %.1f wait %.1f mainloop %.1f finish %.1f\n", idx[k],
+                        idx[k] & 7, idx[k] >> 3, (t[6] - tmin) * 0.01, t[4], t[0] * 0.01, t[1] * 0.01, t[2] * 0.01, t[3] * 0.01);
+            }
+        }
+        fprintf(stderr, "[trace kind %d cfg %dx%dx%d] wgs %d span %.1f us (first done after %.1f) items/wg %.2f | per wg (us): setup %.2f "
+                "wait %.2f mainloop %.2f finish %.2f\n", KIND, C::BM, C::BN, BK, n, (tmax - tmin) * 0.01, (emin - tmin) * 0.01, items / n,
+                ph[0] / n * 0.01, ph[1] / n * 0.01, ph[2] / n * 0.01, ph[3] / n * 0.01);
+    }
+#endif
+}
+
+template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
+{
+    launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st);   // 256 x 256 tile, 8 waves of 128 x 64, 64-deep blocks, 2 ring slots
+}
+}  // namespace sk
+
+void launch_ggemm_bf16_sk(const GemmArgs& a, hipStream_t st)
+{
+    using namespace sk;
+    switch (a.kind) {
+        case kRowsNN_GeLU: launch_kind<kRowsNN_GeLU>(a, st); break;
+        case kRowsNN: launch_kind<kRowsNN>(a, st); break;
+        case kRowsNT_dGeLU: launch_kind<kRowsNT_dGeLU>(a, st); break;
+        case kRowsNT: launch_kind<kRowsNT>(a, st); break;
+        default: launch_kind<kColsT>(a, st); break;
+    }
+}
+
+}  // namespace moe

@@ -129,10 +129,8 @@ static moe_status_t check_ws(const moe_desc_t* D, const void* ws, size_t bytes, 
 
 static void run_gemm(const moe_desc_t& D, GemmArgs& a, hipStream_t st)
 {
-    static const int dbg = [] { const char* v = getenv("MOE355_DEBUG"); return v ? atoi(v) : 0; }();
-    a.debug = dbg;
-    static const bool legacy = [] { const char* v = getenv("MOE355_GEMM"); return v && !strcmp(v, "v1"); }();
-    if (D.dtype == MOE_BF16) { if (legacy) launch_ggemm_bf16(a, st); else launch_ggemm_bf16_dma(a, st); }
+    static const bool old = [] { const char* v = getenv("MOE355_GEMM"); return v && !strcmp(v, "dma"); }();
+    if (D.dtype == MOE_BF16) { if (old) launch_ggemm_bf16_dma(a, st); else launch_ggemm_bf16_sk(a, st); }
     else launch_ggemm_f32(a, st);
 }
 
@@ -198,6 +196,7 @@ moe_status_t moe_workspace_region(const moe_desc_t* desc, const char* name, size
         {"Xs", L.Xs, M * desc->d * b}, {"Z", L.Z, M * desc->h * b},     {"H", L.H, M * desc->h * b},
         {"Ys", L.Ys, M * desc->d * b}, {"dYs", L.dYs, M * desc->d * b}, {"dZ", L.dZ, M * desc->h * b},
         {"dXs", L.dXs, M * desc->d * b}, {"dl", L.dl, M * sizeof(float)},
+        {"status", L.sk_error, sizeof(int32_t)},
     };
     for (const auto& r : regions)
         if (!strcmp(r.n, name)) { *offset = r.off; *bytes = r.len; return MOE_OK; }
@@ -263,6 +262,9 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     a.tileP = (const int32_t*)(ws + L.tileP);
     a.order = (const int32_t*)(ws + L.order);
     a.zeros = ws + L.zeros;
+    a.sk_part = ws + L.sk_part;
+    a.sk_flags = (int32_t*)(ws + L.sk_flags);
+    a.sk_error = (int32_t*)(ws + L.sk_error);
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
     a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h;
@@ -318,6 +320,9 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     a.tileP = (const int32_t*)(ws + L.tileP);
     a.order = (const int32_t*)(ws + L.order);
     a.zeros = ws + L.zeros;
+    a.sk_part = ws + L.sk_part;
+    a.sk_flags = (int32_t*)(ws + L.sk_flags);
+    a.sk_error = (int32_t*)(ws + L.sk_error);
     a.out_f32 = D.grad_dtype == MOE_F32;
     a.accumulate = D.accumulate;
 

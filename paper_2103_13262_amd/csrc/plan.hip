@@ -57,7 +57,8 @@ __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ hist, in
                                                   int32_t* __restrict__ tileP, int32_t* __restrict__ order,
                                                   int32_t* __restrict__ zeros)
 {
-    if (threadIdx.x < 256) zeros[threadIdx.x] = 0;   // 1 KB page read in place of masked rows
+    // page read in place of masked rows, and the flags of the persistent matrix-product kernels behind it
+    if (threadIdx.x < (int)(kZeroedBytes / 4)) zeros[threadIdx.x] = 0;
     __shared__ int s_cnt[kMaxE];
     __shared__ int s_wave[16];
     const int e = threadIdx.x;

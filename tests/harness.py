@@ -8,18 +8,24 @@ from paper_2103_13262_amd.synth import Workload, make_inputs
 TOL = {"f32": 1e-4, "bf16": 2e-2}   # max relative error stated for fp32 / bf16 outputs and gradients
 
 
-def rel_err(got, ref):
-    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref)): elementwise relative error with the
-    tensor's RMS as floor, so elements that are tiny by cancellation do not dominate."""
+def rel_err(got, ref, rms=None):
+    """max_i |got_i - ref_i| / (|ref_i| + rms(ref)): the smallest tol for which every element meets
+    |got - ref| <= tol * |ref| + tol * rms(ref), i.e. the usual relative-plus-absolute closeness test
+    with the absolute term tied to the tensor's RMS, so elements that are tiny by cancellation do not
+    dominate.  `rms` overrides the RMS (a block of a tensor judged against the whole tensor's RMS).
+
+    (With max(|ref_i|, rms) as denominator, a path that stores its intermediates in bf16 and sums
+    exactly already reaches 1.9e-2 on the skewed parity case: that form leaves the stated 2e-2 no room.)"""
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
     if ref.size == 0:
         return 0.0
-    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms is None:
+        rms = float(np.sqrt(np.mean(ref * ref)))
     if rms == 0.0:
         return 0.0 if not np.any(got) else float("inf")
-    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rms)))
+    return float(np.max(np.abs(got - ref) / (np.abs(ref) + rms)))
 
 
 def to_torch(a, dtype_name, device):
@@ -90,6 +96,11 @@ class GpuRun:
         g = lambda t, n: t.cpu().numpy()[:n]
         return dict(idx=b.topk_idx.cpu().numpy(), w=b.topk_w.cpu().numpy(), counts=g(b.counts, w.E),
                     offsets=g(b.offsets, w.E + 1), pos=g(b.pos, M), perm=g(b.perm, M))
+
+    def status(self):
+        """The workspace's error word (0 unless a kernel's bounded wait ran out)."""
+        off, n = B.moe_workspace_region(self.desc, "status")
+        return int(self.buf.workspace[off:off + n].view(self.torch.int32).cpu()[0])
 
     def region(self, name):
         """A named workspace intermediate as float64 numpy [rows, width]."""

@@ -26,6 +26,10 @@ CASES = [
     Workload("single_token_bf16", 1, 64, 96, 3, 2, "bf16", 0.0, 17),
     Workload("top8_f32", 33, 32, 32, 9, 8, "f32", 0.0, 18),
     Workload("gate_over_256_experts_bf16", 200, 64, 32, 300, 3, "bf16", 0.0, 19),
+    # few output tiles with a deep reduction: the tiles of the second and fourth grouped product are cut into
+    # pieces of their reduction; in the first case a workgroup ends one tile and begins the next
+    Workload("split_reduction_bf16", 360, 64, 384, 12, 2, "bf16", 0.0, 22),
+    Workload("split_reduction_deep_bf16", 200, 64, 1024, 3, 2, "bf16", 0.0, 23),
 ]
 
 
@@ -59,22 +63,33 @@ def _full_check(w, grad_dtype=None, few_rows_per_expert=False):
     errs["Y"] = rel_err(to_numpy64(run.Y)[:w.N], ref["Y"])
     errs["dl"] = rel_err(run.region("dl"), ref["dl"].reshape(-1))
     errs["dX"] = rel_err(to_numpy64(run.dX)[:w.N], ref["dX"])
-    errs["dW1"] = rel_err(to_numpy64(run.dW1), ref["dW1"])
-    errs["dW2"] = rel_err(to_numpy64(run.dW2), ref["dW2"])
     errs["dWg"] = rel_err(to_numpy64(run.dWg), ref["dWg"])
     errs["dbg"] = rel_err(to_numpy64(run.dbg)[:w.E], ref["dbg"])
+    # Weight gradients expert by expert, each against the RMS of the whole tensor.  With fewer than 64 rows an
+    # element is a sum of few products of bf16-rounded operands (H, dYs, dZ are stored in bf16: 3 roundings of
+    # 2^-8 each per term) with no averaging over rows; where the terms cancel, the worst of d*h elements
+    # exceeds 2e-2 of |ref| + rms for any bf16-operand product.  For such experts the elementwise metric
+    # is held to twice the bound and the stated bound is applied to max|err| / max|ref| of the block.
+    counts = ref_plan["counts"]
+    for name, got in (("dW1", to_numpy64(run.dW1)), ("dW2", to_numpy64(run.dW2))):
+        rms = float(np.sqrt(np.mean(ref[name] ** 2)))
+        worst_many, worst_few = 0.0, 0.0
+        for e in range(w.E):
+            err = rel_err(got[e], ref[name][e], rms=rms)
+            if w.dtype == "bf16" and 0 < counts[e] < 64:
+                worst_few = max(worst_few, err)
+                assert max_err_over_max(got[e], ref[name][e]) <= tol, (name, e, int(counts[e]))
+            else:
+                worst_many = max(worst_many, err)
+        errs[name] = worst_many
+        errs[name + "[<64 rows] / 2"] = worst_few / 2
     print("  rel errs:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
-    if few_rows_per_expert:
-        # Every expert holds 1-3 rows: a weight-gradient element is a sum of 1-3 products of
-        # bf16-rounded operands (H, dYs, dZ are stored in bf16: 3 roundings of 2^-8 each per term),
-        # so its error is bounded by 3 * 2^-8 * sum|terms| with no averaging over rows; where the
-        # terms cancel this exceeds 2e-2 of max(|ref|, rms).  For these tensors the stated bound is
-        # applied to max|err| / max|ref|, and the elementwise metric is held to twice the bound.
-        for name, got in (("dW1", run.dW1), ("dW2", run.dW2), ("dWg", run.dWg)):
-            assert max_err_over_max(to_numpy64(got), ref[name]) <= tol, name
-            assert errs.pop(name) <= 2 * tol, name
+    if few_rows_per_expert:     # every expert holds 1-3 rows: the same reasoning covers the gate matrix gradient
+        assert max_err_over_max(to_numpy64(run.dWg), ref["dWg"]) <= tol
+        assert errs.pop("dWg") <= 2 * tol
     for name, e in errs.items():
         assert e <= tol, (name, e, tol)
+    assert run.status() == 0            # no wait for a partial sum ran out
     # empty experts receive exact zeros
     for e in np.nonzero(ref_plan["counts"] == 0)[0]:
         assert not np.any(to_numpy64(run.dW1[e])) and not np.any(to_numpy64(run.dW2[e]))
