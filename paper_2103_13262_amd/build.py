@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe355.so")
-SOURCES = ["moe_api.hip", "gate_topk.hip", "plan.hip", "rowmove.hip", "ggemm_f32.hip", "ggemm_bf16_dma.hip", "ggemm_bf16_sk.hip"]
+SOURCES = ["moe_api.hip", "gate_topk.hip", "plan.hip", "rowmove.hip", "ggemm_f32.hip", "ggemm_bf16_sk.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall",
@@ -33,6 +33,8 @@ def _compile(src, extra):
 
 
 def build_library(extra_flags=(), verbose=False):
+    """extra_flags: e.g. ["-DMOE355_DEV_TRACE"] for a development build whose grouped-GEMM launches
+    synchronise and print per-workgroup phase times to stderr (never the build that is benchmarked)."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         results = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))

@@ -124,7 +124,6 @@ struct GemmArgs {
     long long* trace; // development builds only: per-workgroup phase times (8 words per workgroup) or NULL
 };
 void launch_ggemm_f32(const GemmArgs& a, hipStream_t st);
-void launch_ggemm_bf16_dma(const GemmArgs& a, hipStream_t st);
 void launch_ggemm_bf16_sk(const GemmArgs& a, hipStream_t st);
 
 // ---- small device helpers ------------------------------------------------------------------

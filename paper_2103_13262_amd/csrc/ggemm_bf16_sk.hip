@@ -51,7 +51,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef unsigned short u16;
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-constexpr int kMinSplitBlocks = 4;              // a stream-K piece is at least this many reduction blocks
+constexpr int kMinSplitBlocks = 8;              // a stream-K piece is at least this many (full-cost) reduction blocks: handing a partial sum
+                                                // on costs about as much time as 6 blocks, and the hand-overs of one tile form a chain
+constexpr int kMinBlockCost8 = 7;               // cost floor of a block with few valid rows, in eighths of a full block
+                                                // (measured: the operand loads, not the matrix cores, set the pace)
 constexpr int kActLo = (127 - 11) << 7;         // bf16 bit pattern of 2^-11
 constexpr int kActHi = (127 + 3) << 7;          // bf16 bit pattern of 2^3
 constexpr int kActEntries = kActHi - kActLo;    // table entries per sign
@@ -186,7 +189,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     const int xcd = blockIdx.x & 7, wj = blockIdx.x >> 3, W = gridDim.x >> 3;
     const int32_t* P = g.tileP + tile_height_index(BM) * (g.E + 1);
     long start = 0, n_dp = 0;        // rows kinds: first tile of this XCD's share; number of whole-tile items
-    int rem = 0, S = 0, Wp = 0;      // stream-K: left-over tiles, their blocks, participating workgroups
+    int rem = 0, Wp = 0;             // stream-K: left-over tiles, participating workgroups
     int nkT = 0;                     // rows kinds: reduction blocks per tile
     int sk_a = 0, sk_cur = 0;        // stream-K blocks of this workgroup not yet done: [sk_a, sk_cur)
     long dp_i, dp_stride;            // next whole-tile item and the stride to the one after
@@ -201,9 +204,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         rem = (int)(n_x % W);
         if (rem * 10 >= W * 9) rem = 0;       // a nearly full last round is not worth splitting
         n_dp = n_x - rem;
-        S = rem * nkT;
-        Wp = rem ? min(W, max(1, S / kMinSplitBlocks)) : 0;
-        if (wj < Wp) { sk_a = (int)((long)wj * S / Wp); sk_cur = (int)((long)(wj + 1) * S / Wp); }
         dp_i = wj; dp_stride = W;
     } else {
         tpe = ntm * ntn;
@@ -211,33 +211,35 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         else { n_dp = (long)g.E * tpe; dp_i = blockIdx.x; dp_stride = gridDim.x; }
     }
 
-    auto decode_rows = [&](long L, Item& it) {
+    // Tile number L (rows kinds) -> expert, row block inside the expert, column block.  Order inside an expert:
+    // groups of up to GM row blocks; inside a group the row block runs fastest, then the column block, so that
+    // tiles that run at the same time on one XCD share operand panels.
+    auto locate = [&](long L, int& e, int& mt, int& nt) {
         int lo = 0, hi = g.E;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if ((long)P[mid] * ntn <= L) lo = mid; else hi = mid;
         }
-        const int e = lo;
+        e = lo;
         const int mte = P[e + 1] - P[e];
         const int local = (int)(L - (long)P[e] * ntn);
-        // Order inside an expert: groups of up to GM row blocks; inside a group the row block runs fastest,
-        // then the column block, so that tiles that run at the same time on one XCD share operand panels.
         constexpr int GM = 8;
-        int nt, mt;
-        {
-            const int full = mte / GM, per_group = GM * ntn;
-            const int gi = local / per_group;
-            if (gi < full) {
-                const int r = local - gi * per_group;
-                nt = r / GM;
-                mt = gi * GM + (r - nt * GM);
-            } else {
-                const int remm = mte - full * GM;
-                const int r = local - full * per_group;
-                nt = r / remm;
-                mt = full * GM + (r - nt * remm);
-            }
+        const int full = mte / GM, per_group = GM * ntn;
+        const int gi = local / per_group;
+        if (gi < full) {
+            const int r = local - gi * per_group;
+            nt = r / GM;
+            mt = gi * GM + (r - nt * GM);
+        } else {
+            const int remm = mte - full * GM;
+            const int r = local - full * per_group;
+            nt = r / remm;
+            mt = full * GM + (r - nt * remm);
         }
+    };
+    auto decode_rows = [&](long L, Item& it) {
+        int e, mt, nt;
+        locate(L, e, mt, nt);
         const long r0 = (long)g.offsets[e] + (long)mt * BM;
         const int n0 = nt * BN;
         it.A = (const u16*)g.A + r0 * g.K;  it.lda = g.K;
@@ -247,6 +249,41 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         it.c_off = (size_t)r0 * g.Nout + n0;
         it.Mt = min(BM, g.counts[e] - mt * BM);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.K;
     };
+    if constexpr (KIND != kColsT) {
+        if (rem) {
+            // The left-over tiles are cut so that every workgroup gets the same estimated time rather than the same
+            // number of blocks: a block of a tile with few valid rows costs less (its 32-row blocks without a valid
+            // row are skipped), down to the floor set by loading the operands.  Lane i looks at left-over tile i.
+            int w8 = 0;                                   // cost of one block of this lane's tile, in eighths of a full block
+            if (lane < rem) {
+                int e, mt, nt;
+                locate(start + lane, e, mt, nt);
+                const int rows = min(BM, g.counts[e] - mt * BM);
+                w8 = max(kMinBlockCost8, ((rows + 31) / 32) * 8 / (BM / 32));
+            }
+            int incl = w8 * nkT;                          // inclusive prefix of the tiles' costs
+#pragma unroll
+            for (int dlt = 1; dlt < 64; dlt <<= 1) {
+                const int up = __shfl_up(incl, dlt, 64);
+                if (lane >= dlt) incl += up;
+            }
+            const int Sw = __builtin_amdgcn_readlane(incl, 63);
+            Wp = min(W, max(1, Sw / (8 * kMinSplitBlocks)));
+            // cost position -> block number in the row of left-over tiles (tile * nkT + block), rounded down to a block
+            auto to_block = [&](int pos) {
+                const unsigned long long before = __ballot(incl <= pos);          // tiles that end at or before pos
+                const int tile = __popcll(before);
+                if (tile >= rem) return rem * nkT;
+                const int excl = tile ? __builtin_amdgcn_readlane(incl, tile - 1) : 0;
+                const int w = __builtin_amdgcn_readlane(w8, tile);
+                return tile * nkT + (pos - excl) / w;
+            };
+            if (wj < Wp) {
+                sk_a = to_block((int)((long)wj * Sw / Wp));
+                sk_cur = wj + 1 == Wp ? rem * nkT : to_block((int)((long)(wj + 1) * Sw / Wp));
+            }
+        }
+    }
     auto next_item = [&](Item& it) -> bool {
         if constexpr (KIND != kColsT) {
             if (sk_cur > sk_a) {       // stream-K pieces, last one first
@@ -784,7 +821,9 @@ void launch_cfg(const GemmArgs& a, hipStream_t st)
 
 template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
 {
-    launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st);   // 256 x 256 tile, 8 waves of 128 x 64, 64-deep blocks, 2 ring slots
+    // 256 x 256 tile, 8 waves of 128 x 64, 64-deep blocks, 2 ring slots.  (32-deep blocks in 4 slots bring the main
+    // loop 10 % closer to its pace without cache misses but lengthen everything around it: no gain on the whole.)
+    launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st);
 }
 }  // namespace sk
 

@@ -129,8 +129,7 @@ static moe_status_t check_ws(const moe_desc_t* D, const void* ws, size_t bytes, 
 
 static void run_gemm(const moe_desc_t& D, GemmArgs& a, hipStream_t st)
 {
-    static const bool old = [] { const char* v = getenv("MOE355_GEMM"); return v && !strcmp(v, "dma"); }();
-    if (D.dtype == MOE_BF16) { if (old) launch_ggemm_bf16_dma(a, st); else launch_ggemm_bf16_sk(a, st); }
+    if (D.dtype == MOE_BF16) launch_ggemm_bf16_sk(a, st);
     else launch_ggemm_f32(a, st);
 }
 

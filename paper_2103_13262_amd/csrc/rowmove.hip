@@ -175,15 +175,19 @@ __global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs,
 // owns one 16-byte column piece and walks the rows of its piece; a second kernel adds an expert's pieces
 // in ascending order.
 template <typename T>
-__global__ __launch_bounds__(128) void dwg_partial(const void* __restrict__ Xs, const float* __restrict__ dl,
+__global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, const float* __restrict__ dl,
                                                    const int32_t* __restrict__ perm, const int32_t* __restrict__ counts,
                                                    const int32_t* __restrict__ offsets, const int32_t* __restrict__ P64,
                                                    float* __restrict__ part, float* __restrict__ bpart, int E, int d,
                                                    int cpr)
 {
+    // 128 column threads x 4 row groups: group q walks rows 16q .. 16q+15 of the piece; the groups' sums are added
+    // in the order ((0 + 1) + 2) + 3, so the result does not depend on timing.
     constexpr int V = Vec<T>::N;
+    __shared__ float s_g[64];
+    __shared__ float s_acc[3][128][V];
     const int piece = blockIdx.x;
-    if (piece >= P64[E]) return;
+    if (piece >= P64[E]) return;          // uniform over the workgroup
     int lo = 0, hi = E;                   // largest e with P64[e] <= piece
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -192,23 +196,52 @@ __global__ __launch_bounds__(128) void dwg_partial(const void* __restrict__ Xs, 
     const int e = lo;
     const int r0 = offsets[e] + (piece - P64[e]) * 64;
     const int r1 = min(r0 + 64, offsets[e] + counts[e]);
-    const int c = blockIdx.y * 128 + threadIdx.x;
-    if (c >= cpr) return;
-    float acc[V], sdl = 0.f;
+    if (threadIdx.x < 64) s_g[threadIdx.x] = r0 + (int)threadIdx.x < r1 ? dl[perm[r0 + threadIdx.x]] : 0.f;
+    __syncthreads();
+    const int ct = threadIdx.x & 127, q = threadIdx.x >> 7;
+    const int c = blockIdx.y * 128 + ct;
+    const bool active = c < cpr;
+    float acc[V];
 #pragma unroll
     for (int u = 0; u < V; ++u) acc[u] = 0.f;
-    for (int r = r0; r < r1; ++r) {
-        const float g = dl[perm[r]];
-        float v[V];
-        Vec<T>::load(Xs, (size_t)r * cpr + c, v);
+    if (active) {
 #pragma unroll
-        for (int u = 0; u < V; ++u) acc[u] = fmaf(g, v[u], acc[u]);
-        sdl += g;
+        for (int i0 = 0; i0 < 16; i0 += 4) {
+            float v[4][V];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {     // rows past the end of the piece contribute g = 0; their loads are skipped
+                const int r = r0 + q * 16 + i0 + i;
+#pragma unroll
+                for (int u = 0; u < V; ++u) v[i][u] = 0.f;
+                if (r < r1) Vec<T>::load(Xs, (size_t)r * cpr + c, v[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float g = s_g[q * 16 + i0 + i];
+#pragma unroll
+                for (int u = 0; u < V; ++u) acc[u] = fmaf(g, v[i][u], acc[u]);
+            }
+        }
     }
-    float* dst = part + (size_t)piece * d + (size_t)c * V;
+    if (q > 0) {
 #pragma unroll
-    for (int u = 0; u < V; ++u) dst[u] = acc[u];
-    if (c == 0) bpart[piece] = sdl;
+        for (int u = 0; u < V; ++u) s_acc[q - 1][ct][u] = acc[u];
+    }
+    __syncthreads();
+    if (q == 0 && active) {
+#pragma unroll
+        for (int g = 0; g < 3; ++g)
+#pragma unroll
+            for (int u = 0; u < V; ++u) acc[u] += s_acc[g][ct][u];
+        float* dst = part + (size_t)piece * d + (size_t)c * V;
+#pragma unroll
+        for (int u = 0; u < V; ++u) dst[u] = acc[u];
+        if (c == 0) {
+            float sdl = 0.f;
+            for (int i = 0; i < 64; ++i) sdl += s_g[i];
+            bpart[piece] = sdl;
+        }
+    }
 }
 
 template <typename G>
@@ -295,7 +328,7 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     if (D.dtype == MOE_BF16) {
         using T = unsigned short;
         hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
-        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
+        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
         if (D.grad_dtype == MOE_BF16)
             hipLaunchKernelGGL(dwg_final<unsigned short>, dim3(fg), dim3(256), 0, st, (const float*)part,
                                (const float*)bpart, P64, (unsigned short*)dWg, dbg, D.d, D.E, D.accumulate);
@@ -307,7 +340,7 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     } else {
         using T = float;
         hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
-        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(128), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
+        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
         hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
                            P64, (float*)dWg, dbg, D.d, D.E, D.accumulate);
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
