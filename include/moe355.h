@@ -78,7 +78,8 @@ typedef struct {
 } moe_plan_t;
 
 /* Bytes of device workspace the three calls below need for this problem (expert-contiguous
- * activations Xs, Z, H, Ys, their gradients, the tile schedule and reduction scratch).
+ * activations Xs, Z, H, Ys, their gradients, the tile schedule, reduction scratch and, for bf16,
+ * 64 MiB in which the matrix-product workgroups hand partial sums to one another).
  * Returns 0 if desc is NULL or not supported. Host-only; touches no device. */
 size_t moe_workspace_bytes(const moe_desc_t *desc);
 
@@ -87,8 +88,9 @@ size_t moe_workspace_bytes(const moe_desc_t *desc);
  * count / offset step of Section 3.2).
  *   X  device [N,d] dtype;  Wg device [d,E] dtype;  bg device [E] float or NULL (= zeros).
  *   plan: host struct holding six device arrays, all written.
- *   workspace: device, >= moe_workspace_bytes(); the tile schedule written here is read by
- *   moe_forward / moe_backward, which must receive the same workspace.
+ *   workspace: device, >= moe_workspace_bytes(); the tile schedule written here (and the flags
+ *   and status word cleared here) are used by moe_forward / moe_backward, which must receive the
+ *   same workspace.  Calls that share a workspace must not overlap in time.
  * The selection is exact: logits are accumulated in fp64, so indices, counts and the
  * permutation are those of exact arithmetic unless two logits agree to ~1e-15 relative.
  */
@@ -100,7 +102,9 @@ moe_status_t moe_plan(const moe_desc_t *desc, const void *X, const void *Wg, con
  * (Section 4 reordering of Algorithm 1's loop).
  *   W1 device [E,d,h], W2 device [E,h,d] dtype;  b1, b2 must be NULL (expert biases unsupported).
  *   Y device [N,d] dtype, written.
- * Leaves Xs, Z (pre-activation), H = GeLU(Z) and Ys in the workspace for moe_backward.
+ * Leaves Xs, Z (pre-activation), H and Ys in the workspace for moe_backward.  bf16: Z is the
+ * rounded accumulator, H = z * Phi(Z) with z the fp32 accumulator and Phi the normal CDF taken at
+ * the stored Z (the erf GeLU up to that rounding inside Phi, which moves H by less than 6e-4).
  */
 moe_status_t moe_forward(const moe_desc_t *desc, const moe_plan_t *plan, const void *X, const void *W1,
                          const void *W2, const void *b1, const void *b2, void *Y, void *workspace,
@@ -126,7 +130,9 @@ moe_status_t moe_backward(const moe_desc_t *desc, const moe_plan_t *plan, const 
  * expert outputs before the weighted gather (these four are valid after moe_forward);
  * "dYs" [M,d], "dZ" [M,h], "dXs" [M,d] (dtype elements) and "dl" [M] float, the gradient of the
  * selected logits (valid after moe_backward).  Rows are in expert-contiguous order (row r holds
- * assignment perm[r]).  Returns MOE_ERR_INVALID_ARG for an unknown name.
+ * assignment perm[r]).  "status": one int32, cleared by moe_plan and set to 1 if a workgroup's
+ * bounded wait for another workgroup's partial sum ever ran out (never, by construction; results
+ * of that call are then invalid).  Returns MOE_ERR_INVALID_ARG for an unknown name.
  */
 moe_status_t moe_workspace_region(const moe_desc_t *desc, const char *name, size_t *offset, size_t *bytes);
 

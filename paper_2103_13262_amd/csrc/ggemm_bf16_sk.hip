@@ -303,11 +303,16 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
             }
             return false;
         } else {
-            if (dp_i >= n_dp) return false;
-            int ord, q;
-            if (per) { ord = (int)(dp_i / per); q = xcd * per + (int)(dp_i - (long)ord * per); }
-            else     { ord = (int)(dp_i / tpe); q = (int)(dp_i - (long)ord * tpe); }
+            // Tiles are listed by descending reduction length (experts by descending row count).  Rounds alternate
+            // direction, so the workgroup that got the longest tile of one round gets the shortest of the next.
+            const long round = dp_i / dp_stride, lanepos = dp_i - round * dp_stride;
+            const long item = round * dp_stride + ((round & 1) ? dp_stride - 1 - lanepos : lanepos);
+            if (round * dp_stride >= n_dp) return false;
             dp_i += dp_stride;
+            if (item >= n_dp) return false;   // (only in the last round)
+            int ord, q;
+            if (per) { ord = (int)(item / per); q = xcd * per + (int)(item - (long)ord * per); }
+            else     { ord = (int)(item / tpe); q = (int)(item - (long)ord * tpe); }
             const int e = g.order[ord];
             const int m0 = (q / ntn) * BM, n0 = (q % ntn) * BN;
             const long off = g.offsets[e];
