@@ -51,7 +51,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef unsigned short u16;
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-constexpr int kMinSplitBlocks = 8;              // a stream-K piece is at least this many (full-cost) reduction blocks: handing a partial sum
+constexpr int kMinSplitBlocks = 16;             // a stream-K piece is at least this many (full-cost) reduction blocks: handing a partial sum
                                                 // on costs about as much time as 6 blocks, and the hand-overs of one tile form a chain
 constexpr int kMinBlockCost8 = 7;               // cost floor of a block with few valid rows, in eighths of a full block
                                                 // (measured: the operand loads, not the matrix cores, set the pace)
@@ -593,10 +593,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         const float* patch_r[PASSES]; int prow[PASSES], pcol[PASSES]; bool pok[PASSES];
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
-            const int q = lane_ + p * 64;
+            const int q = min(lane_ + p * 64, 8 * CPRW - 1);   // (lanes beyond the slab's pieces idle on a copy of the last)
             prow[p] = q / CPRW;
             pcol[p] = wn * TN * 32 + (q % CPRW) * 8;
-            pok[p] = q < 8 * CPRW && pcol[p] < it.Nt;
+            pok[p] = lane_ + p * 64 < 8 * CPRW && pcol[p] < it.Nt;
             patch_r[p] = patch + prow[p] * PITCH + (q % CPRW) * 8;
         }
         struct Slab { float4 lo[PASSES], hi[PASSES]; };
@@ -828,6 +828,12 @@ template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
 {
     // 256 x 256 tile, 8 waves of 128 x 64, 64-deep blocks, 2 ring slots.  (32-deep blocks in 4 slots bring the main
     // loop 10 % closer to its pace without cache misses but lengthen everything around it: no gain on the whole.)
+    // Many small experts (fewer than 96 rows on average): 64 x 256 tiles, 8 waves of 64 x 32, 3 ring slots, so that a
+    // tile is not mostly rows that do not exist.  (The weight gradients keep the large tile: their tile spans the
+    // weight matrix, not the expert's rows.)
+    if constexpr (KIND != kColsT) {
+        if (a.M < 96L * a.E) { launch_cfg<KIND, 1, 8, 2, 1, 3, 64>(a, st); return; }
+    }
     launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st);
 }
 }  // namespace sk
