@@ -130,6 +130,16 @@ def main():
     peak = PEAK_BF16_TFLOPS if bf else PEAK_FP32_TFLOPS
     for n, (c, t) in gemm.items():
         kern[n]["tflops"] = flops_launch / (t / c * 1e-3) / 1e12
+    # the data-movement kernels against the HBM roofline: algorithmic bytes per launch / mean duration
+    eb = 2 if bf else 4
+    Md, Nd = w.M * w.d * eb, w.N * w.d * eb
+    moved = {"gate_topk": Nd, "scatter": 2 * Md, "combine": Md + Nd, "dcombine": Nd + 2 * Md, "gate_bwd": 2 * Md + 2 * Nd}
+    for n, nbytes in moved.items():
+        if n in prof and prof[n][0]:
+            c, t = prof[n]
+            kern[n]["algorithmic_bytes"] = nbytes
+            kern[n]["gbps"] = nbytes / (t / c * 1e-3) / 1e9
+            kern[n]["frac_of_hbm_peak"] = kern[n]["gbps"] / PEAK_HBM_GBS
     roofline = {"bound": "mfma" if bf else "alu", "kernel": "ggemm_dma_kernel (6 launches per step)" if bf
                 else "ggemm_f32_kernel (6 launches per step)",
                 "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,

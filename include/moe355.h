@@ -125,6 +125,38 @@ moe_status_t moe_backward(const moe_desc_t *desc, const moe_plan_t *plan, const 
                           void *dW1, void *dW2, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The data-movement steps on their own, so that any expert network can sit between them (the
+ * paper's layer takes an arbitrary expert module: Section 3.1; the reordering itself is Section 4,
+ * "scatter" before the experts and "gather" after them).  All four take a plan written by moe_plan
+ * for the same desc (desc->h is not used) and caller-owned buffers in the expert-contiguous row
+ * order of the plan: row pos[a] belongs to assignment a = t*k + j, rows of expert e are
+ * offsets[e] .. offsets[e+1]-1.  M = N*k.  Same status codes and stream rules as above.
+ *
+ *   moe_scatter:          Xs[pos[a],:] = X[a / k,:]                    X [N,d] -> Xs [M,d] (copy)
+ *   moe_gather:           Y[t,:] = sum_j topk_w[t,j] * Ys[pos[t*k+j],:]   Ys [M,d] -> Y [N,d]
+ *                         (slots in ascending order, fp32 accumulation)
+ *   moe_gather_backward:  dYs[pos[a],:] = topk_w[a] * dY[t,:]  and the gradient of the selected logits,
+ *                         dl[t,j] = w_j (dw_j - sum_i w_i dw_i) with dw_j = <dY[t,:], Ys[pos[t*k+j],:]>
+ *                         (the weights are a softmax over the k selected logits; exact zeros for k = 1).
+ *                         dY [N,d], Ys [M,d] -> dYs [M,d] dtype, dl [M] float in assignment order.
+ *   moe_scatter_backward: dX[t,:] = sum_j dXs[pos[t*k+j],:] + sum_j dl[t,j] * Wg[:,idx[t,j]]   (expert path
+ *                         + gate path), dWg[:,e] (+)= sum over assignments of e of dl * x, dbg likewise.
+ *                         Wg [d,E], Xs [M,d] (as written by moe_scatter), dXs [M,d], dl [M] -> dX [N,d] dtype,
+ *                         dWg [d,E] grad_dtype and dbg [E] float (or NULL), written or accumulated per
+ *                         desc->accumulate.  Needs a workspace of moe_workspace_bytes() for its fixed-order
+ *                         reduction; the workspace of moe_plan may be used.
+ * With N == 0 nothing is launched except that moe_scatter_backward still writes dWg / dbg (zeros, or
+ * leaves them when accumulating).
+ */
+moe_status_t moe_scatter(const moe_desc_t *desc, const moe_plan_t *plan, const void *X, void *Xs, void *stream);
+moe_status_t moe_gather(const moe_desc_t *desc, const moe_plan_t *plan, const void *Ys, void *Y, void *stream);
+moe_status_t moe_gather_backward(const moe_desc_t *desc, const moe_plan_t *plan, const void *dY, const void *Ys,
+                                 void *dYs, float *dl, void *stream);
+moe_status_t moe_scatter_backward(const moe_desc_t *desc, const moe_plan_t *plan, const void *Wg, const void *Xs,
+                                  const void *dXs, const float *dl, void *dX, void *dWg, float *dbg,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Where a named intermediate lives inside the workspace (host-only; touches no device).
  * Names: "Xs" [M,d] scattered inputs, "Z" [M,h] pre-activations, "H" [M,h] GeLU(Z), "Ys" [M,d]
  * expert outputs before the weighted gather (these four are valid after moe_forward);

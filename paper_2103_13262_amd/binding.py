@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe355.so")
 MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP = 0, -1, -2, -3, -4
 MOE_F32, MOE_BF16 = 0, 1
 EXPORTS = ("moe_workspace_bytes", "moe_workspace_region", "moe_plan", "moe_forward", "moe_backward",
+           "moe_scatter", "moe_gather", "moe_gather_backward", "moe_scatter_backward",
            "moe_last_error", "moe_profile_enable", "moe_profile_read")
 
 
@@ -64,6 +65,11 @@ def lib():
         L.moe_forward.argtypes = [C.POINTER(MoeDesc), C.POINTER(MoePlan), vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.moe_backward.restype = C.c_int
         L.moe_backward.argtypes = [C.POINTER(MoeDesc), C.POINTER(MoePlan)] + [vp] * 11 + [C.c_size_t, vp]
+        for name, nptr in (("moe_scatter", 3), ("moe_gather", 3), ("moe_gather_backward", 5)):
+            getattr(L, name).argtypes = [C.POINTER(MoeDesc), C.POINTER(MoePlan)] + [vp] * nptr
+            getattr(L, name).restype = C.c_int
+        L.moe_scatter_backward.argtypes = [C.POINTER(MoeDesc), C.POINTER(MoePlan)] + [vp] * 8 + [C.c_size_t, vp]
+        L.moe_scatter_backward.restype = C.c_int
         L.moe_workspace_region.restype = C.c_int
         L.moe_workspace_region.argtypes = [C.POINTER(MoeDesc), C.c_char_p, C.POINTER(C.c_size_t),
                                            C.POINTER(C.c_size_t)]
@@ -139,6 +145,25 @@ def moe_backward(desc, plan, X, Wg, W1, W2, dY, dX, dWg, dbg, dW1, dW2, workspac
     _check(lib().moe_backward(C.byref(desc), C.byref(plan), _p(X), _p(Wg), _p(W1), _p(W2), _p(dY), _p(dX),
                               _p(dWg), _p(dbg), _p(dW1), _p(dW2), _p(workspace), C.c_size_t(workspace_bytes),
                               C.c_void_p(stream)))
+
+
+def moe_scatter(desc, plan, X, Xs, stream=0):
+    _check(lib().moe_scatter(C.byref(desc), None if plan is None else C.byref(plan), _p(X), _p(Xs), C.c_void_p(stream)))
+
+
+def moe_gather(desc, plan, Ys, Y, stream=0):
+    _check(lib().moe_gather(C.byref(desc), None if plan is None else C.byref(plan), _p(Ys), _p(Y), C.c_void_p(stream)))
+
+
+def moe_gather_backward(desc, plan, dY, Ys, dYs, dl, stream=0):
+    _check(lib().moe_gather_backward(C.byref(desc), None if plan is None else C.byref(plan), _p(dY), _p(Ys), _p(dYs), _p(dl),
+                                     C.c_void_p(stream)))
+
+
+def moe_scatter_backward(desc, plan, Wg, Xs, dXs, dl, dX, dWg, dbg, workspace, workspace_bytes, stream=0):
+    _check(lib().moe_scatter_backward(C.byref(desc), None if plan is None else C.byref(plan), _p(Wg), _p(Xs), _p(dXs), _p(dl), _p(dX),
+                                      _p(dWg), _p(dbg), _p(workspace), C.c_size_t(workspace_bytes),
+                                      C.c_void_p(stream)))
 
 
 class MoeLayerBuffers:

@@ -356,4 +356,70 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     return check_launch("gate backward");
 }
 
+moe_status_t moe_scatter(const moe_desc_t* desc, const moe_plan_t* plan, const void* X, void* Xs, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    MOE_REQUIRE_PTR(X);
+    MOE_REQUIRE_PTR(Xs);
+    if (desc->N == 0) return MOE_OK;
+    launch_scatter(*desc, X, plan->perm, Xs, (hipStream_t)stream);
+    return check_launch("scatter");
+}
+
+moe_status_t moe_gather(const moe_desc_t* desc, const moe_plan_t* plan, const void* Ys, void* Y, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    MOE_REQUIRE_PTR(Ys);
+    MOE_REQUIRE_PTR(Y);
+    if (desc->N == 0) return MOE_OK;
+    launch_combine(*desc, Ys, plan->topk_w, plan->pos, Y, (hipStream_t)stream);
+    return check_launch("gather");
+}
+
+moe_status_t moe_gather_backward(const moe_desc_t* desc, const moe_plan_t* plan, const void* dY, const void* Ys,
+                                 void* dYs, float* dl, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    MOE_REQUIRE_PTR(dY);
+    MOE_REQUIRE_PTR(Ys);
+    MOE_REQUIRE_PTR(dYs);
+    if (!dl || (reinterpret_cast<uintptr_t>(dl) & 3u)) { set_error("dl is NULL or not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    if (desc->N == 0) return MOE_OK;
+    launch_dcombine(*desc, dY, Ys, plan->topk_w, plan->pos, dYs, dl, (hipStream_t)stream);
+    return check_launch("gather backward");
+}
+
+moe_status_t moe_scatter_backward(const moe_desc_t* desc, const moe_plan_t* plan, const void* Wg, const void* Xs,
+                                  const void* dXs, const float* dl, void* dX, void* dWg, float* dbg,
+                                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    MOE_REQUIRE_PTR(Wg);
+    MOE_REQUIRE_PTR(dWg);
+    if (dbg && (reinterpret_cast<uintptr_t>(dbg) & 3u)) { set_error("dbg is not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    WsLayout L;
+    if ((s = check_ws(desc, workspace, workspace_bytes, &L)) != MOE_OK) return s;
+    if (desc->N > 0) {
+        MOE_REQUIRE_PTR(Xs);
+        MOE_REQUIRE_PTR(dXs);
+        MOE_REQUIRE_PTR(dX);
+        if (!dl || (reinterpret_cast<uintptr_t>(dl) & 3u)) { set_error("dl is NULL or not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    }
+    launch_gate_bwd(*desc, L, Xs, dXs, Wg, dl, plan->topk_idx, plan->pos, plan->perm, plan->counts, plan->offsets, dX,
+                    dWg, dbg, (char*)workspace, (hipStream_t)stream);
+    return check_launch("scatter backward");
+}
+
 }  // extern "C"

@@ -83,6 +83,12 @@ def test_null_misaligned_and_small_workspace_arguments():
         lambda: B.moe_plan(d, FAKE, FAKE, None, B.make_plan(FAKE, None, FAKE, FAKE, FAKE, FAKE), FAKE, ws),
         lambda: B.moe_forward(d, plan, FAKE, None, FAKE, None, None, FAKE, FAKE, ws),    # W1 NULL
         lambda: B.moe_backward(d, plan, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, ws),
+        lambda: B.moe_scatter(d, plan, None, FAKE),                                      # X NULL
+        lambda: B.moe_scatter(d, plan, FAKE, FAKE + 4),                                  # Xs misaligned
+        lambda: B.moe_gather(d, plan, FAKE, None),                                       # Y NULL
+        lambda: B.moe_gather_backward(d, plan, FAKE, FAKE, FAKE, None),                  # dl NULL
+        lambda: B.moe_gather_backward(d, None, FAKE, FAKE, FAKE, FAKE),                  # plan NULL
+        lambda: B.moe_scatter_backward(d, plan, FAKE, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, ws),   # dWg NULL
     ]
     for c in cases:
         with pytest.raises(B.MoeError) as ei:
@@ -90,6 +96,9 @@ def test_null_misaligned_and_small_workspace_arguments():
         assert ei.value.status == B.MOE_ERR_INVALID_ARG
     with pytest.raises(B.MoeError) as ei:
         B.moe_plan(d, FAKE, FAKE, None, plan, FAKE, ws - 1)
+    assert ei.value.status == B.MOE_ERR_WORKSPACE
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_scatter_backward(d, plan, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, ws - 1)
     assert ei.value.status == B.MOE_ERR_WORKSPACE
     with pytest.raises(B.MoeError) as ei:                                                 # expert biases
         B.moe_forward(d, plan, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, ws)

@@ -304,3 +304,75 @@ def test_token_subsets_and_tracked_experts_are_consistent():
     np.testing.assert_array_equal(ot["dW1"], full["dW1"][trk])
     np.testing.assert_array_equal(ot["dW2"], full["dW2"][trk])
     assert "Y" not in ot and "dWg" not in ot
+
+
+# ------------------------------------------------------------------ scatter / gather on their own
+def _reorder_setup(seed, N=9, d=5, h=6, E=4, k=2):
+    from oracle import moe_reorder as ro
+
+    p = _rand_problem(seed, N=N, d=d, h=h, E=E, k=k)
+    ref = orc.layer(p, want_internals=True)
+    idx, w, _ = orc.gate(p)
+    counts, offsets, pos, perm = orc.plan(idx, E)
+    return ro, p, ref, idx, w, counts, offsets, pos, perm
+
+
+def test_scatter_then_gather_with_unit_weight_sums_is_identity():
+    ro, p, ref, idx, w, counts, offsets, pos, perm = _reorder_setup(71)
+    X = p.X
+    Xs = ro.scatter(X, pos, p.k)
+    np.testing.assert_array_equal(Xs[pos], np.repeat(X, p.k, axis=0))     # a pure copy, row by row
+    for e in range(p.E):                                                   # segments hold the rows of their expert
+        assert np.all(idx.reshape(-1)[perm[offsets[e]:offsets[e + 1]]] == e)
+    np.testing.assert_allclose(ro.gather(Xs, w, pos), X, rtol=0, atol=1e-14)   # the weights sum to one
+
+
+def test_scatter_experts_gather_reproduces_the_per_token_oracle():
+    """Batched route (scatter, one dense FFN per expert segment in numpy, gather, and the same backwards)
+    against the per-token loop of moe_oracle.c: two independent statements of Algorithm 1."""
+    ro, p, ref, idx, w, counts, offsets, pos, perm = _reorder_setup(72, N=11, E=5, k=3)
+    X, Wg, W1, W2, dY = p.X, p.Wg, p.W1, p.W2, p.dY      # float64 in this problem
+    Xs = ro.scatter(X, pos, p.k)
+    Ys = np.empty_like(Xs)
+    for e in range(p.E):
+        seg = slice(offsets[e], offsets[e + 1])
+        Ys[seg] = _ffn(Xs[seg], W1[e], W2[e])
+    np.testing.assert_allclose(ro.gather(Ys, w, pos), ref["Y"], rtol=1e-12, atol=1e-13)
+    dYs, dl = ro.gather_backward(dY, Ys, w, pos)
+    np.testing.assert_allclose(dl, ref["dl"], rtol=1e-10, atol=1e-12)
+    dXs = np.empty_like(Xs)
+    for e in range(p.E):
+        seg = slice(offsets[e], offsets[e + 1])
+        Z = Xs[seg] @ W1[e]
+        dZ = (dYs[seg] @ W2[e].T) * _gelu_grad(Z)
+        dXs[seg] = dZ @ W1[e].T
+    dX, dWg, dbg = ro.scatter_backward(Wg, Xs, dXs, dl, idx, pos)
+    np.testing.assert_allclose(dX, ref["dX"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dWg, ref["dWg"], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dbg, ref["dbg"], rtol=1e-10, atol=1e-12)
+
+
+def test_gather_gradients_match_central_differences():
+    ro, p, ref, idx, w, counts, offsets, pos, perm = _reorder_setup(73, N=4, d=3, E=3, k=2)
+    g = np.random.default_rng(5)
+    Ys = g.standard_normal((p.N * p.k, p.d))
+    dY = g.standard_normal((p.N, p.d))
+    logits = g.standard_normal((p.N, p.k))          # the k selected logits of each token
+    sm = lambda l: softmax(l, axis=1)
+    loss = lambda ys, l: float(np.sum(dY * ro.gather(ys, sm(l), pos)))
+    dYs, dl = ro.gather_backward(dY, Ys, sm(logits), pos)
+    eps = 1e-6
+    num = np.zeros_like(Ys)
+    for i in np.ndindex(*Ys.shape):
+        a, b = Ys.copy(), Ys.copy()
+        a[i] += eps
+        b[i] -= eps
+        num[i] = (loss(a, logits) - loss(b, logits)) / (2 * eps)
+    np.testing.assert_allclose(dYs, num, rtol=1e-6, atol=1e-8)
+    numl = np.zeros_like(logits)
+    for i in np.ndindex(*logits.shape):
+        a, b = logits.copy(), logits.copy()
+        a[i] += eps
+        b[i] -= eps
+        numl[i] = (loss(Ys, a) - loss(Ys, b)) / (2 * eps)
+    np.testing.assert_allclose(dl, numl, rtol=1e-6, atol=1e-8)
