@@ -53,8 +53,6 @@ typedef unsigned short u16;
 
 constexpr int kMinSplitBlocks = 16;             // a stream-K piece is at least this many (full-cost) reduction blocks: handing a partial sum
                                                 // on costs about as much time as 6 blocks, and the hand-overs of one tile form a chain
-constexpr int kMinBlockCost8 = 7;               // cost floor of a block with few valid rows, in eighths of a full block
-                                                // (measured: the operand loads, not the matrix cores, set the pace)
 constexpr int kActLo = (127 - 11) << 7;         // bf16 bit pattern of 2^-11
 constexpr int kActHi = (127 + 3) << 7;          // bf16 bit pattern of 2^3
 constexpr int kActEntries = kActHi - kActLo;    // table entries per sign
@@ -189,7 +187,9 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     const int xcd = blockIdx.x & 7, wj = blockIdx.x >> 3, W = gridDim.x >> 3;
     const int32_t* P = g.tileP + tile_height_index(BM) * (g.E + 1);
     long start = 0, n_dp = 0;        // rows kinds: first tile of this XCD's share; number of whole-tile items
-    int rem = 0, Wp = 0;             // stream-K: left-over tiles, participating workgroups
+    int rem = 0, Wp = 0;             // left-over tiles of this XCD; workgroups taking part in their reduction split
+    int row_f = 1;                   // left-over tiles cut into this many row slices instead
+    bool row_item = false;           // this workgroup still has to do row slice wj % row_f of left-over tile wj / row_f
     int nkT = 0;                     // rows kinds: reduction blocks per tile
     int sk_a = 0, sk_cur = 0;        // stream-K blocks of this workgroup not yet done: [sk_a, sk_cur)
     long dp_i, dp_stride;            // next whole-tile item and the stride to the one after
@@ -237,55 +237,45 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
             mt = full * GM + (r - nt * remm);
         }
     };
-    auto decode_rows = [&](long L, Item& it) {
+    // slice s of f: only rows s*BM/f .. (s+1)*BM/f - 1 of the tile (f = 1: the whole tile)
+    auto decode_rows = [&](long L, Item& it, int slice = 0, int f = 1) {
         int e, mt, nt;
         locate(L, e, mt, nt);
-        const long r0 = (long)g.offsets[e] + (long)mt * BM;
+        const int rows_per = BM / f, row_off = slice * rows_per;
+        const long r0 = (long)g.offsets[e] + (long)mt * BM + row_off;
         const int n0 = nt * BN;
         it.A = (const u16*)g.A + r0 * g.K;  it.lda = g.K;
         const u16* Be = (const u16*)g.B + (size_t)e * g.K * g.Nout;
         if constexpr (C::B_TRANS) { it.B = Be + n0; it.ldb = g.Nout; }
         else                      { it.B = Be + (size_t)n0 * g.K; it.ldb = g.K; }
         it.c_off = (size_t)r0 * g.Nout + n0;
-        it.Mt = min(BM, g.counts[e] - mt * BM);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.K;
+        it.Mt = min(rows_per, g.counts[e] - mt * BM - row_off);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.K;
     };
     if constexpr (KIND != kColsT) {
         if (rem) {
-            // The left-over tiles are cut so that every workgroup gets the same estimated time rather than the same
-            // number of blocks: a block of a tile with few valid rows costs less (its 32-row blocks without a valid
-            // row are skipped), down to the floor set by loading the operands.  Lane i looks at left-over tile i.
-            int w8 = 0;                                   // cost of one block of this lane's tile, in eighths of a full block
-            if (lane < rem) {
-                int e, mt, nt;
-                locate(start + lane, e, mt, nt);
-                const int rows = min(BM, g.counts[e] - mt * BM);
-                w8 = max(kMinBlockCost8, ((rows + 31) / 32) * 8 / (BM / 32));
-            }
-            int incl = w8 * nkT;                          // inclusive prefix of the tiles' costs
-#pragma unroll
-            for (int dlt = 1; dlt < 64; dlt <<= 1) {
-                const int up = __shfl_up(incl, dlt, 64);
-                if (lane >= dlt) incl += up;
-            }
-            const int Sw = __builtin_amdgcn_readlane(incl, 63);
-            Wp = min(W, max(1, Sw / (8 * kMinSplitBlocks)));
-            // cost position -> block number in the row of left-over tiles (tile * nkT + block), rounded down to a block
-            auto to_block = [&](int pos) {
-                const unsigned long long before = __ballot(incl <= pos);          // tiles that end at or before pos
-                const int tile = __popcll(before);
-                if (tile >= rem) return rem * nkT;
-                const int excl = tile ? __builtin_amdgcn_readlane(incl, tile - 1) : 0;
-                const int w = __builtin_amdgcn_readlane(w8, tile);
-                return tile * nkT + (pos - excl) / w;
-            };
-            if (wj < Wp) {
-                sk_a = to_block((int)((long)wj * Sw / Wp));
-                sk_cur = wj + 1 == Wp ? rem * nkT : to_block((int)((long)(wj + 1) * Sw / Wp));
+            if (nkT >= 2 * kMinSplitBlocks) {
+                // long reductions: the left-over tiles' blocks, laid end to end, in equal contiguous ranges.  (Ranges
+                // of equal estimated time instead - blocks of tiles with few valid rows are cheaper - change nothing
+                // measurable: such a block still costs 7/8 of a full one, the operand loads set the pace.)
+                const int S = rem * nkT;
+                Wp = min(W, max(1, S / kMinSplitBlocks));
+                if (wj < Wp) { sk_a = (int)((long)wj * S / Wp); sk_cur = (int)((long)(wj + 1) * S / Wp); }
+            } else {
+                // short reductions: a hand-over of partial sums would cost as much as the piece itself; when at most
+                // half of the workgroups would get a left-over tile, the tiles are cut by rows instead (no partial sums)
+                row_f = rem * 4 <= W && BM >= 128 ? 4 : rem * 2 <= W && BM >= 64 ? 2 : 1;
+                row_item = wj < rem * row_f;
             }
         }
     }
     auto next_item = [&](Item& it) -> bool {
         if constexpr (KIND != kColsT) {
+            if (row_item) {
+                row_item = false;
+                decode_rows(start + wj / row_f, it, wj % row_f, row_f);
+                it.kb0 = 0;  it.kb1 = nkT;  it.owner = 1;
+                if (it.Mt > 0) return true;      // (a slice past the tile's last row holds nothing)
+            }
             if (sk_cur > sk_a) {       // stream-K pieces, last one first
                 const int tt = (sk_cur - 1) / nkT;
                 const int seg0 = max(sk_a, tt * nkT);
