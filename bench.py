@@ -31,6 +31,10 @@ def parse():
     ap.add_argument("--custom", default=None, metavar="N,d,h,E,k[,zipf_s]",
                     help="a bf16 layer of another shape (sweeps of experts / rows per expert); overrides --workload")
     ap.add_argument("--cpu-sample-tokens", type=int, default=-1, help="tokens of the oracle sample (0: skip)")
+    ap.add_argument("--sweep-experts", default=None, metavar="E1,E2,...",
+                    help="the paper's single-GPU experiment (Section 5.2, computation time against the number of "
+                         "experts at n_b=4096, d_m=1024, d_h=4096, k=2): one JSON line per expert count with the "
+                         "forward and backward times; replaces the default output")
     return ap.parse_args()
 
 
@@ -73,6 +77,23 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.lib()   # raises if the HIP library has not been built: there is no fallback
+    if a.sweep_experts:
+        for E in (int(v) for v in a.sweep_experts.split(",")):
+            a.custom, a.cpu_sample_tokens = f"4096,1024,4096,{E},2", 0
+            out = run(a, torch, B, WORKLOADS, make_inputs)
+            kt = {n: v["avg_us"] * v["launches_per_step"] for n, v in out["kernels"].items()}
+            fwd = sum(kt.get(n, 0.0) for n in ("scatter", "ggemm_fc1_gelu", "ggemm_fc2", "combine"))
+            plan = sum(kt.get(n, 0.0) for n in ("gate_topk", "plan"))
+            print(json.dumps({"sweep": "experts", "n_b": 4096, "d_m": 1024, "d_h": 4096, "k": 2, "n_e": E,
+                              "ms_per_step": out["ms_per_step"], "gate_and_plan_ms": plan / 1e3, "forward_ms": fwd / 1e3,
+                              "backward_ms": (sum(kt.values()) - fwd - plan) / 1e3, "tokens_per_s": out["value"],
+                              "grouped_gemm_tflops": out["roofline"]["achieved"]}), flush=True)
+            torch.cuda.empty_cache()
+        return
+    print(json.dumps(run(a, torch, B, WORKLOADS, make_inputs)))
+
+
+def run(a, torch, B, WORKLOADS, make_inputs):
     w = WORKLOADS[a.workload]
     if a.custom:
         from paper_2103_13262_amd.synth import Workload
@@ -163,7 +184,7 @@ def main():
         n_cpu = int(max(8, min(w.N, 2.5e11 / (12.0 * w.k * w.d * w.h))))
     if n_cpu > 0:
         out["cpu_baseline"] = cpu_baseline(w, inputs, n_cpu)
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":
