@@ -178,10 +178,6 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
 
     float* patch = (float*)(smem + C::RING) + wave * (8 * PITCH);
     const float* act = (const float*)(smem + C::RING + C::PATCH_BYTES);
-    if constexpr (C::TABLE) {   // visible to all waves after the first barrier, long before the first epilogue
-        float* w = (float*)(smem + C::RING + C::PATCH_BYTES);
-        for (int i = tid; i < 2 * kActEntries; i += NT) w[i] = act_entry<KIND>(i);
-    }
 
     // ---------------- schedule of this workgroup ----------------
     const int xcd = blockIdx.x & 7, wj = blockIdx.x >> 3, W = gridDim.x >> 3;
@@ -700,6 +696,12 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     Item cur;
     bool have = next_item(cur);
     if (have) start_item(cur);
+    if constexpr (C::TABLE) {
+        // built while the first blocks are on their way; visible to all waves after the first barrier, long
+        // before the first epilogue (every item of these kinds has at least one block)
+        float* w = (float*)(smem + C::RING + C::PATCH_BYTES);
+        for (int i = tid; i < 2 * kActEntries; i += NT) w[i] = act_entry<KIND>(i);
+    }
     TRACE_PHASE(0);
     while (have) {
 #pragma unroll
