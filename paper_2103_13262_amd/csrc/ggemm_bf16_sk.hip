@@ -190,6 +190,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     int sk_a = 0, sk_cur = 0;        // stream-K blocks of this workgroup not yet done: [sk_a, sk_cur)
     long dp_i, dp_stride;            // next whole-tile item and the stride to the one after
     int tpe = 0, per = 0;            // weight gradients: tiles per expert, and per expert and XCD
+    bool by_expert = false;          // weight gradients: every XCD works on whole experts (decided by the plan step)
     if constexpr (KIND != kColsT) {
         const long T = (long)P[g.E] * ntn;
         const long base = T >> 3;
@@ -203,7 +204,9 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         dp_i = wj; dp_stride = W;
     } else {
         tpe = ntm * ntn;
-        if ((tpe & 7) == 0) { per = tpe >> 3; n_dp = (long)g.E * per; dp_i = wj; dp_stride = W; }
+        by_expert = *g.by_expert != 0;
+        if (by_expert) { n_dp = (long)((g.E + 7) / 8) * tpe; dp_i = wj; dp_stride = W; }
+        else if ((tpe & 7) == 0) { per = tpe >> 3; n_dp = (long)g.E * per; dp_i = wj; dp_stride = W; }
         else { n_dp = (long)g.E * tpe; dp_i = blockIdx.x; dp_stride = gridDim.x; }
     }
 
@@ -291,14 +294,25 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         } else {
             // Tiles are listed by descending reduction length (experts by descending row count).  Rounds alternate
             // direction, so the workgroup that got the longest tile of one round gets the shortest of the next.
-            const long round = dp_i / dp_stride, lanepos = dp_i - round * dp_stride;
-            const long item = round * dp_stride + ((round & 1) ? dp_stride - 1 - lanepos : lanepos);
-            if (round * dp_stride >= n_dp) return false;
-            dp_i += dp_stride;
-            if (item >= n_dp) return false;   // (only in the last round)
+            // Which tiles an XCD gets: when the experts' sizes allow it (by_expert), whole experts - the expert of
+            // rank r goes to XCD r%8, every other group of eight reversed - so that each operand panel is fetched
+            // into one L2 only; otherwise an eighth of every expert's tiles.
             int ord, q;
-            if (per) { ord = (int)(item / per); q = xcd * per + (int)(item - (long)ord * per); }
-            else     { ord = (int)(item / tpe); q = (int)(item - (long)ord * tpe); }
+            for (;;) {
+                const long round = dp_i / dp_stride, lanepos = dp_i - round * dp_stride;
+                const long item = round * dp_stride + ((round & 1) ? dp_stride - 1 - lanepos : lanepos);
+                if (round * dp_stride >= n_dp) return false;
+                dp_i += dp_stride;
+                if (item >= n_dp) return false;   // (only in the last round)
+                if (by_expert) {
+                    const int grp = (int)(item / tpe);
+                    ord = 8 * grp + ((grp & 1) ? 7 - xcd : xcd);
+                    q = (int)(item - (long)grp * tpe);
+                    if (ord >= g.E) continue;     // (the last group of eight may be incomplete)
+                } else if (per) { ord = (int)(item / per); q = xcd * per + (int)(item - (long)ord * per); }
+                else            { ord = (int)(item / tpe); q = (int)(item - (long)ord * tpe); }
+                break;
+            }
             const int e = g.order[ord];
             const int m0 = (q / ntn) * BM, n0 = (q % ntn) * BN;
             const long off = g.offsets[e];

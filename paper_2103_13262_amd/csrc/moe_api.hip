@@ -264,6 +264,7 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     a.sk_part = ws + L.sk_part;
     a.sk_flags = (int32_t*)(ws + L.sk_flags);
     a.sk_error = (int32_t*)(ws + L.sk_error);
+    a.by_expert = (const int32_t*)(ws + L.sk_error) + 1;
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
     a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h;
@@ -322,6 +323,7 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     a.sk_part = ws + L.sk_part;
     a.sk_flags = (int32_t*)(ws + L.sk_flags);
     a.sk_error = (int32_t*)(ws + L.sk_error);
+    a.by_expert = (const int32_t*)(ws + L.sk_error) + 1;
     a.out_f32 = D.grad_dtype == MOE_F32;
     a.accumulate = D.accumulate;
 

@@ -92,6 +92,26 @@ __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ hist, in
         }
         order[rank] = e;
     }
+    // Can the weight-gradient products give every XCD whole experts (expert of rank r to XCD r%8, every other
+    // group of eight reversed)?  Then each operand panel is fetched by one XCD only.  Only if the reduction blocks
+    // that each XCD would get stay within 10 % of the mean; the answer sits behind the status word.
+    __shared__ int s_xcd[8];
+    if (threadIdx.x < 8) s_xcd[threadIdx.x] = 0;
+    __syncthreads();
+    if (e < E) {
+        int rank = 0;
+        for (int o = 0; o < E; ++o) {
+            const int c = s_cnt[o];
+            rank += (c > cnt || (c == cnt && o < e)) ? 1 : 0;
+        }
+        atomicAdd(&s_xcd[(rank >> 3) & 1 ? 7 - (rank & 7) : rank & 7], (cnt + 63) / 64);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int mx = 0, sum = 0;
+        for (int x = 0; x < 8; ++x) { mx = max(mx, s_xcd[x]); sum += s_xcd[x]; }
+        zeros[kZeroedBytes / 4 - 63] = (E >= 8 && (long)mx * 80 <= (long)sum * 11) ? 1 : 0;
+    }
 }
 
 __global__ __launch_bounds__(256) void plan_rank(const int32_t* __restrict__ idx, long M, int E, int nbits,
