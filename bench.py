@@ -35,6 +35,10 @@ def parse():
                     help="the paper's single-GPU experiment (Section 5.2, computation time against the number of "
                          "experts at n_b=4096, d_m=1024, d_h=4096, k=2): one JSON line per expert count with the "
                          "forward and backward times; replaces the default output")
+    ap.add_argument("--sweep-rows", default=None, metavar="N1,N2,...",
+                    help="throughput of the grouped matrix products against the batch an expert sees (the paper's "
+                         "Section 4 figure of GeMM throughput against problem size): token counts at d_m=1024, "
+                         "d_h=4096, 16 experts, k=2, i.e. N/8 rows per expert; one JSON line per count")
     return ap.parse_args()
 
 
@@ -88,6 +92,16 @@ def main():
                               "ms_per_step": out["ms_per_step"], "gate_and_plan_ms": plan / 1e3, "forward_ms": fwd / 1e3,
                               "backward_ms": (sum(kt.values()) - fwd - plan) / 1e3, "tokens_per_s": out["value"],
                               "grouped_gemm_tflops": out["roofline"]["achieved"]}), flush=True)
+            torch.cuda.empty_cache()
+        return
+    if a.sweep_rows:
+        for N in (int(v) for v in a.sweep_rows.split(",")):
+            a.custom, a.cpu_sample_tokens = f"{N},1024,4096,16,2", 0
+            out = run(a, torch, B, WORKLOADS, make_inputs)
+            print(json.dumps({"sweep": "rows", "d_m": 1024, "d_h": 4096, "n_e": 16, "k": 2, "n_b": N,
+                              "rows_per_expert": N * 2 / 16, "ms_per_step": out["ms_per_step"],
+                              "tokens_per_s": out["value"], "grouped_gemm_tflops": out["roofline"]["achieved"],
+                              "grouped_gemm_avg_launch_us": out["roofline"]["avg_launch_us"]}), flush=True)
             torch.cuda.empty_cache()
         return
     print(json.dumps(run(a, torch, B, WORKLOADS, make_inputs)))
