@@ -175,11 +175,19 @@ def run(a, torch, B, WORKLOADS, make_inputs):
             kern[n]["algorithmic_bytes"] = nbytes
             kern[n]["gbps"] = nbytes / (t / c * 1e-3) / 1e9
             kern[n]["frac_of_hbm_peak"] = kern[n]["gbps"] / PEAK_HBM_GBS
-    roofline = {"bound": "mfma" if bf else "alu", "kernel": "ggemm_dma_kernel (6 launches per step)" if bf
+    clock_mhz = None
+    if bf:   # the shader clock the last grouped product ran at (the chip does not hold its 2.4 GHz under matrix-core load)
+        off, n = B.moe_workspace_region(desc, "clock")
+        cyc, ticks = (int(v) for v in buf.workspace[off:off + n].view(torch.int64).cpu())
+        clock_mhz = 100.0 * cyc / ticks if ticks > 0 else None
+    roofline = {"bound": "mfma" if bf else "alu", "kernel": "ggemm_sk_kernel (6 launches per step)" if bf
                 else "ggemm_f32_kernel (6 launches per step)",
                 "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                 "traffic": MEASURED_HBM_BYTES_PER_GEMM_LAUNCH.get(w.name) if not a.custom else None,
-                "flops_per_launch": flops_launch, "avg_launch_us": avg_launch_ms * 1e3}
+                "flops_per_launch": flops_launch, "avg_launch_us": avg_launch_ms * 1e3,
+                # context: the same fraction against 256 CUs x 4096 flop/clk at the clock measured during the launch
+                "shader_clock_mhz": clock_mhz,
+                "frac_of_peak_at_measured_clock": (achieved / (256 * 4096 * clock_mhz * 1e6 / 1e12)) if clock_mhz else None}
 
     out = {
         "metric": METRIC, "value": w.N / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,

@@ -164,7 +164,10 @@ moe_status_t moe_scatter_backward(const moe_desc_t *desc, const moe_plan_t *plan
  * selected logits (valid after moe_backward).  Rows are in expert-contiguous order (row r holds
  * assignment perm[r]).  "status": one int32, cleared by moe_plan and set to 1 if a workgroup's
  * bounded wait for another workgroup's partial sum ever ran out (never, by construction; results
- * of that call are then invalid).  Returns MOE_ERR_INVALID_ARG for an unknown name.
+ * of that call are then invalid).  "clock": two int64 written by the last bf16 matrix-product launch,
+ * shader cycles and ticks of the 100 MHz reference clock over the lifetime of one of its workgroups
+ * (their ratio x 100 is the shader clock in MHz the launch ran at).  Returns MOE_ERR_INVALID_ARG for an
+ * unknown name.
  */
 moe_status_t moe_workspace_region(const moe_desc_t *desc, const char *name, size_t *offset, size_t *bytes);
 

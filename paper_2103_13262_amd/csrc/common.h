@@ -120,6 +120,7 @@ struct GemmArgs {
     int32_t* sk_flags;     // one flag per persistent workgroup, all zero between launches
     int32_t* sk_error;
     const int32_t* by_expert;  // 1: the weight-gradient products give every XCD whole experts (decided by the plan step)
+    long long* clock_probe;    // [2]: shader cycles and 100 MHz ticks of workgroup 0 of the last launch
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT
     long long* trace; // development builds only: per-workgroup phase times (8 words per workgroup) or NULL

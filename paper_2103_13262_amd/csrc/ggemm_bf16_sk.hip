@@ -179,6 +179,8 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     float* patch = (float*)(smem + C::RING) + wave * (8 * PITCH);
     const float* act = (const float*)(smem + C::RING + C::PATCH_BYTES);
 
+    const long long probe_cycles0 = clock64(), probe_ticks0 = wall_clock64();
+
     // ---------------- schedule of this workgroup ----------------
     const int xcd = blockIdx.x & 7, wj = blockIdx.x >> 3, W = gridDim.x >> 3;
     const int32_t* P = g.tileP + tile_height_index(BM) * (g.E + 1);
@@ -749,6 +751,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
 #ifdef MOE355_DEV_TRACE
         ++tr_items;
 #endif
+    }
+    if (blockIdx.x == 0 && tid == 0) {   // shader cycles and 100 MHz ticks this workgroup lived: the clock the launch ran at
+        g.clock_probe[0] = clock64() - probe_cycles0;
+        g.clock_probe[1] = wall_clock64() - probe_ticks0;
     }
 #ifdef MOE355_DEV_TRACE
     if (g.trace && tid == 0) {

@@ -196,6 +196,7 @@ moe_status_t moe_workspace_region(const moe_desc_t* desc, const char* name, size
         {"Ys", L.Ys, M * desc->d * b}, {"dYs", L.dYs, M * desc->d * b}, {"dZ", L.dZ, M * desc->h * b},
         {"dXs", L.dXs, M * desc->d * b}, {"dl", L.dl, M * sizeof(float)},
         {"status", L.sk_error, sizeof(int32_t)},
+        {"clock", L.sk_error + 8, 2 * sizeof(long long)},
     };
     for (const auto& r : regions)
         if (!strcmp(r.n, name)) { *offset = r.off; *bytes = r.len; return MOE_OK; }
@@ -265,6 +266,7 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     a.sk_flags = (int32_t*)(ws + L.sk_flags);
     a.sk_error = (int32_t*)(ws + L.sk_error);
     a.by_expert = (const int32_t*)(ws + L.sk_error) + 1;
+    a.clock_probe = (long long*)(ws + L.sk_error + 8);
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
     a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h;
@@ -324,6 +326,7 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     a.sk_flags = (int32_t*)(ws + L.sk_flags);
     a.sk_error = (int32_t*)(ws + L.sk_error);
     a.by_expert = (const int32_t*)(ws + L.sk_error) + 1;
+    a.clock_probe = (long long*)(ws + L.sk_error + 8);
     a.out_f32 = D.grad_dtype == MOE_F32;
     a.accumulate = D.accumulate;
 
