@@ -89,7 +89,8 @@ struct Cfg {
     static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LA = A_BYTES / 1024 / NW, LB = B_BYTES / 1024 / NW;   // wave-level loads per wave and stage
     static constexpr int RING = STAGES * STAGE_BYTES;
-    static constexpr int PITCH = TN * 32 + 8;                 // floats per patch row: rows 4 apart are 32 banks apart
+    static constexpr int TNG = TN < 2 ? TN : 2;               // accumulator columns that pass through the patch together
+    static constexpr int PITCH = TNG * 32 + 8;                // floats per patch row: rows 4 apart are 32 banks apart
     static constexpr int PATCH_BYTES = NW * 8 * PITCH * 4;    // 8 rows per wave
     static constexpr bool TABLE = KIND == kRowsNN_GeLU || KIND == kRowsNT_dGeLU;
     static constexpr int TABLE_BYTES = TABLE ? 2 * kActEntries * 4 : 0;
@@ -583,127 +584,116 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     // next slab may be written into the patch as soon as the reads of the current one have been issued; the
     // loop below keeps the patch traffic of slab s+1 and the table look-ups of slab s-1 in flight while the
     // values of slab s are converted and stored.
-    constexpr int CPRW = TN * 4;                 // 8-column pieces per row of the wave tile
-    static_assert(8 * CPRW <= 64 || (8 * CPRW) % 64 == 0, "pieces per slab");
-    constexpr int PASSES = (8 * CPRW + 63) / 64;
+    constexpr int TNG = C::TNG;                  // accumulator columns per pass through the patch
+    constexpr int CPRW = TNG * 4;                // 8-column pieces per row of a column group
+    static_assert(8 * CPRW <= 64 && TN % TNG == 0, "a slab of a column group is at most one piece per lane");
     auto epilogue = [&](const Fin& it) {
         constexpr bool LOOKUP = C::TABLE;
         const int ldc = g.Nout;
         int lane_ = lane;
         asm volatile("" : "+v"(lane_));   // keeps the address arithmetic of the epilogue out of the main loop's registers
         float* const patch_w = patch + ((lane_ >> 5) * 4) * PITCH + (lane_ & 31);
-        const float* patch_r[PASSES]; int prow[PASSES], pcol[PASSES]; bool pok[PASSES];
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int q = min(lane_ + p * 64, 8 * CPRW - 1);   // (lanes beyond the slab's pieces idle on a copy of the last)
-            prow[p] = q / CPRW;
-            pcol[p] = wn * TN * 32 + (q % CPRW) * 8;
-            pok[p] = lane_ + p * 64 < 8 * CPRW && pcol[p] < it.Nt;
-            patch_r[p] = patch + prow[p] * PITCH + (q % CPRW) * 8;
-        }
-        struct Slab { float4 lo[PASSES], hi[PASSES]; };
-        auto to_patch = [&](int i, int sl) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) patch_w[r * PITCH + j * 32] = acc[i][j][4 * sl + r];
-        };
-        auto from_patch = [&](Slab& v) {
-#pragma unroll
-            for (int p = 0; p < PASSES; ++p) {
-                v.lo[p] = *(const float4*)patch_r[p];
-                v.hi[p] = *(const float4*)(patch_r[p] + 4);
-            }
-        };
+        const int q = min(lane_, 8 * CPRW - 1);      // (lanes beyond the slab's pieces idle on a copy of the last)
+        const int prow = q / CPRW;
+        const float* const patch_r = patch + prow * PITCH + (q % CPRW) * 8;
+        struct Slab { float4 lo, hi; };
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             if (i >= tm_act) break;
             const int row0 = (wm * TM + i) * 32;
-            uint4 zin[4][PASSES];
-            if constexpr (KIND == kRowsNT_dGeLU) {   // saved pre-activations of the whole block, requested up front
 #pragma unroll
-                for (int sl = 0; sl < 4; ++sl)
+            for (int cg = 0; cg < TN / TNG; ++cg) {      // column groups of the wave tile, one after the other
+                const int pcol = (wn * TN + cg * TNG) * 32 + (q % CPRW) * 8;
+                const bool pok = lane_ < 8 * CPRW && pcol < it.Nt;
+                auto to_patch = [&](int sl) {
 #pragma unroll
-                    for (int p = 0; p < PASSES; ++p) {
-                        const int row = row0 + sl * 8 + prow[p];
-                        zin[sl][p] = make_uint4(0, 0, 0, 0);
-                        if (pok[p] && row < it.Mt)
-                            zin[sl][p] = *(const uint4*)((const u16*)g.Zin + it.c_off + (size_t)row * ldc + pcol[p]);
-                    }
-            }
-            Slab cur, nxt;
-            float xs[PASSES][8], fac[PASSES][8];   // values and looked-up factors of the slab before the current one
-            to_patch(i, 0);
-            from_patch(cur);
+                    for (int j = 0; j < TNG; ++j)
 #pragma unroll
-            for (int sl = 0; sl <= 4; ++sl) {
-                if (sl + 1 < 4) { to_patch(i, sl + 1); from_patch(nxt); }
-                if constexpr (LOOKUP) {
-                    if (sl > 0) {   // second half of slab sl-1: its factors have arrived
+                        for (int r = 0; r < 4; ++r) patch_w[r * PITCH + j * 32] = acc[i][cg * TNG + j][4 * sl + r];
+                };
+                auto from_patch = [&](Slab& v) {
+                    v.lo = *(const float4*)patch_r;
+                    v.hi = *(const float4*)(patch_r + 4);
+                };
+                uint4 zin[4];
+                if constexpr (KIND == kRowsNT_dGeLU) {   // saved pre-activations of the whole block, requested up front
 #pragma unroll
-                        for (int p = 0; p < PASSES; ++p) {
-                            const int row = row0 + (sl - 1) * 8 + prow[p];
-                            if (!pok[p] || row >= it.Mt) continue;
-#pragma unroll
-                            for (int t = 0; t < 8; ++t) xs[p][t] *= fac[p][t];
-                            const size_t o = it.c_off + (size_t)row * ldc + pcol[p];
-                            *(uint4*)((u16*)(KIND == kRowsNN_GeLU ? g.C2 : g.C) + o) = pack8(xs[p]);
-                        }
+                    for (int sl = 0; sl < 4; ++sl) {
+                        const int row = row0 + sl * 8 + prow;
+                        zin[sl] = make_uint4(0, 0, 0, 0);
+                        if (pok && row < it.Mt)
+                            zin[sl] = *(const uint4*)((const u16*)g.Zin + it.c_off + (size_t)row * ldc + pcol);
                     }
                 }
-                if (sl == 4) break;
+                Slab cur, nxt;
+                float xs[8], fac[8];   // values and looked-up factors of the slab before the current one
+                to_patch(0);
+                from_patch(cur);
 #pragma unroll
-                for (int p = 0; p < PASSES; ++p) {
-                    const int row = row0 + sl * 8 + prow[p];
-                    if (!pok[p] || row >= it.Mt) continue;
-                    float x[8] = {cur.lo[p].x, cur.lo[p].y, cur.lo[p].z, cur.lo[p].w,
-                                  cur.hi[p].x, cur.hi[p].y, cur.hi[p].z, cur.hi[p].w};
-                    const size_t o = it.c_off + (size_t)row * ldc + pcol[p];
-                    if constexpr (KIND == kRowsNN_GeLU) {
-                        const uint4 zp = pack8(x);
-                        *(uint4*)((u16*)g.C + o) = zp;
-                        const unsigned w[4] = {zp.x, zp.y, zp.z, zp.w};
+                for (int sl = 0; sl <= 4; ++sl) {
+                    if (sl + 1 < 4) { to_patch(sl + 1); from_patch(nxt); }
+                    if constexpr (LOOKUP) {
+                        if (sl > 0) {   // second half of slab sl-1: its factors have arrived
+                            const int row = row0 + (sl - 1) * 8 + prow;
+                            if (pok && row < it.Mt) {
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) {   // H = z Phi(zb): z in fp32, Phi looked up at its bf16 rounding zb
-                            fac[p][2 * t] = act[act_index(w[t])];
-                            fac[p][2 * t + 1] = act[act_index(w[t] >> 16)];
-                        }
-#pragma unroll
-                        for (int t = 0; t < 8; ++t) xs[p][t] = x[t];
-                    } else if constexpr (KIND == kRowsNT_dGeLU) {
-                        const unsigned w[4] = {zin[sl][p].x, zin[sl][p].y, zin[sl][p].z, zin[sl][p].w};
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            fac[p][2 * t] = act[act_index(w[t])];
-                            fac[p][2 * t + 1] = act[act_index(w[t] >> 16)];
-                        }
-#pragma unroll
-                        for (int t = 0; t < 8; ++t) xs[p][t] = x[t];
-                    } else if constexpr (KIND == kColsT) {
-                        if (g.out_f32) {
-                            float4* Cf = (float4*)((float*)g.C + o);
-                            if (g.accumulate) {
-                                const float4 p0 = Cf[0], p1 = Cf[1];
-                                x[0] += p0.x; x[1] += p0.y; x[2] += p0.z; x[3] += p0.w;
-                                x[4] += p1.x; x[5] += p1.y; x[6] += p1.z; x[7] += p1.w;
+                                for (int t = 0; t < 8; ++t) xs[t] *= fac[t];
+                                const size_t o = it.c_off + (size_t)row * ldc + pcol;
+                                *(uint4*)((u16*)(KIND == kRowsNN_GeLU ? g.C2 : g.C) + o) = pack8(xs);
                             }
-                            Cf[0] = make_float4(x[0], x[1], x[2], x[3]);
-                            Cf[1] = make_float4(x[4], x[5], x[6], x[7]);
+                        }
+                    }
+                    if (sl == 4) break;
+                    const int row = row0 + sl * 8 + prow;
+                    if (pok && row < it.Mt) {
+                        float x[8] = {cur.lo.x, cur.lo.y, cur.lo.z, cur.lo.w, cur.hi.x, cur.hi.y, cur.hi.z, cur.hi.w};
+                        const size_t o = it.c_off + (size_t)row * ldc + pcol;
+                        if constexpr (KIND == kRowsNN_GeLU) {
+                            const uint4 zp = pack8(x);
+                            *(uint4*)((u16*)g.C + o) = zp;
+                            const unsigned w[4] = {zp.x, zp.y, zp.z, zp.w};
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {   // H = z Phi(zb): z in fp32, Phi looked up at its bf16 rounding zb
+                                fac[2 * t] = act[act_index(w[t])];
+                                fac[2 * t + 1] = act[act_index(w[t] >> 16)];
+                            }
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) xs[t] = x[t];
+                        } else if constexpr (KIND == kRowsNT_dGeLU) {
+                            const unsigned w[4] = {zin[sl].x, zin[sl].y, zin[sl].z, zin[sl].w};
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                fac[2 * t] = act[act_index(w[t])];
+                                fac[2 * t + 1] = act[act_index(w[t] >> 16)];
+                            }
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) xs[t] = x[t];
+                        } else if constexpr (KIND == kColsT) {
+                            if (g.out_f32) {
+                                float4* Cf = (float4*)((float*)g.C + o);
+                                if (g.accumulate) {
+                                    const float4 p0 = Cf[0], p1 = Cf[1];
+                                    x[0] += p0.x; x[1] += p0.y; x[2] += p0.z; x[3] += p0.w;
+                                    x[4] += p1.x; x[5] += p1.y; x[6] += p1.z; x[7] += p1.w;
+                                }
+                                Cf[0] = make_float4(x[0], x[1], x[2], x[3]);
+                                Cf[1] = make_float4(x[4], x[5], x[6], x[7]);
+                            } else {
+                                uint4* Ch = (uint4*)((u16*)g.C + o);
+                                if (g.accumulate) {
+                                    float prev[8];
+                                    unpack8(*Ch, prev);
+#pragma unroll
+                                    for (int t = 0; t < 8; ++t) x[t] += prev[t];
+                                }
+                                *Ch = pack8(x);
+                            }
                         } else {
-                            uint4* Ch = (uint4*)((u16*)g.C + o);
-                            if (g.accumulate) {
-                                float prev[8];
-                                unpack8(*Ch, prev);
-#pragma unroll
-                                for (int t = 0; t < 8; ++t) x[t] += prev[t];
-                            }
-                            *Ch = pack8(x);
+                            *(uint4*)((u16*)g.C + o) = pack8(x);
                         }
-                    } else {
-                        *(uint4*)((u16*)g.C + o) = pack8(x);
                     }
+                    cur = nxt;
                 }
-                cur = nxt;
             }
         }
     };
