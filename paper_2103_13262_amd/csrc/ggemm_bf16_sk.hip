@@ -829,7 +829,10 @@ void launch_cfg(const GemmArgs& a, hipStream_t st)
 template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
 {
     // 256 x 256 tile, 8 waves of 128 x 64, 64-deep blocks, 2 ring slots.  (32-deep blocks in 4 slots bring the main
-    // loop 10 % closer to its pace without cache misses but lengthen everything around it: no gain on the whole.)
+    // loop 10 % closer to its pace without cache misses but lengthen everything around it: no gain on the whole.
+    // Two workgroups of 4 waves per compute unit, each on a 256 x 128 tile with 32-deep blocks, so that one computes
+    // while the other waits or writes its tile, are 15-20 % slower: they move half as much again into LDS per flop,
+    // and it is that traffic, not the latency of a request, that sets the pace.)
     // Many small experts (fewer than 96 rows on average): 64 x 256 tiles, 8 waves of 64 x 32, 3 ring slots, so that a
     // tile is not mostly rows that do not exist.  (The weight gradients keep the large tile: their tile spans the
     // weight matrix, not the expert's rows.)
