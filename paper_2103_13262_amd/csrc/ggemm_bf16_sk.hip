@@ -22,10 +22,16 @@
 //   k-contiguous source ([row][k]):  LDS row = 2*BK bytes; 16-byte chunk c of row r sits at position
 //       c ^ swz(r); operand reads are ds_read_b128 and free of bank conflicts.
 //   row-contiguous source ([k][row], the reduction index is the slow one: weights in the forward products,
-//       both operands of the weight gradients): LDS keeps the global layout, chunk c of k-row k at position
-//       c ^ 2*(k&3); operands are gathered with ds_read_b64_tr_b16.
+//       both operands of the weight gradients): an LDS row is one k-row (512 bytes: every k-row starts at
+//       bank 0), chunk c of k-row k sits at position swap13(c) ^ 2*(k&3), where swap13 exchanges bits 1 and 3 of
+//       the chunk number; operands are gathered with ds_read_b64_tr_b16.  One such read takes, per 16 lanes,
+//       2 chunks of each of 4 k-rows, and the next 16 lanes take the 2 chunks beside them: the positions of 16
+//       lanes are distinct modulo 8 and those of 32 lanes distinct modulo 16, so the read is free of bank
+//       conflicts whether the LDS serves 128 or 256 bytes per clock.
 // Rows / columns outside a tile's valid extent are fetched from a clamped (valid) address and their results
-// are never stored.  Reduction indices past the end are fetched from a page of zeros.
+// are never stored.  (Not requesting them at all changes nothing measurable: a block of a tile with few valid
+// rows takes as long as the requests for the other operand take to arrive.)  Reduction indices past the end are
+// fetched from a page of zeros.
 //
 // The Gaussian factors of GeLU and GeLU' are looked up at the bf16 value zb that is stored as the
 // pre-activation, so they are functions of 16 bits: an LDS table indexed by the bit pattern (built from erfc /
@@ -57,6 +63,8 @@ constexpr int kActLo = (127 - 11) << 7;         // bf16 bit pattern of 2^-11
 constexpr int kActHi = (127 + 3) << 7;          // bf16 bit pattern of 2^3
 constexpr int kActEntries = kActHi - kActLo;    // table entries per sign
 constexpr int kSpinLimit = 1 << 20;             // bounded wait for a partial sum (on the order of a second)
+
+__device__ __forceinline__ int swap13(int c) { return (c & ~10) | ((c & 2) << 2) | ((c & 8) >> 2); }
 
 template <int BK> __device__ __forceinline__ int swz(int r)
 {
@@ -136,8 +144,9 @@ __device__ __forceinline__ void setup_ptrs(const u16* base, long ld, int valid, 
             krow[i] = c * 8;
         } else {
             constexpr int CPR = R / 8;
+            static_assert(CPR >= 16 && 64 % CPR == 0, "the position code needs 16 chunks per k-row");
             const int kr = j * (64 / CPR) + lane / CPR;
-            int c = (lane % CPR) ^ (2 * (kr & 3));
+            int c = swap13((lane % CPR) ^ (2 * (kr & 3)));
             c = c * 8 < valid ? c : 0;
             ptr[i] = base + (long)kr * ld + c * 8;
             krow[i] = kr;
@@ -391,7 +400,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
             offA[i] = (rb + (lane & 31)) * (BK * 2) + ((((lane >> 5)) ^ swz<BK>(lane & 31)) << 4);
         } else {
             const int s = lane & 15, col = rb + ((lane >> 4) & 1) * 16 + 4 * (s & 3);
-            offA[i] = ((lane >> 5) * 8 + (s >> 2)) * (BM * 2) + ((((col >> 3)) ^ (2 * (s >> 2))) << 4) + (col & 7) * 2;
+            offA[i] = ((lane >> 5) * 8 + (s >> 2)) * (BM * 2) + ((swap13(col >> 3) ^ (2 * (s >> 2))) << 4) + (col & 7) * 2;
         }
     }
 #pragma unroll
@@ -401,7 +410,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
             offB[j] = (rb + (lane & 31)) * (BK * 2) + ((((lane >> 5)) ^ swz<BK>(lane & 31)) << 4);
         } else {
             const int s = lane & 15, col = rb + ((lane >> 4) & 1) * 16 + 4 * (s & 3);
-            offB[j] = ((lane >> 5) * 8 + (s >> 2)) * (BN * 2) + ((((col >> 3)) ^ (2 * (s >> 2))) << 4) + (col & 7) * 2;
+            offB[j] = ((lane >> 5) * 8 + (s >> 2)) * (BN * 2) + ((swap13(col >> 3) ^ (2 * (s >> 2))) << 4) + (col & 7) * 2;
         }
     }
     auto fetchA = [&](const char* tile, int i, int ks) -> bf16x8 {
@@ -451,8 +460,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
                 if (FULL || i < tm_act) a[i] = fetchA(tA, i, ks);
         };
         // One 16-deep MFMA step.  The loads of the block that refills the slot freed at the last barrier are
-        // spread over the KS steps that follow that barrier, one place before each accumulator row.
-        constexpr int SLOTS = KS * TM;
+        // issued during the first step after that barrier, a share before each accumulator row: early, because
+        // they have only until the end of this block to arrive.  (Spread evenly over all the block's steps instead,
+        // the rows kinds run 3-5 % slower.)
+        constexpr int SLOTS = TM;
         auto mma = [&](const bf16x8 (&a)[TM], const bf16x8 (&b)[TN], auto step_c, int load_li) {
             constexpr int STEP = decltype(step_c)::value;
 #pragma unroll
@@ -828,18 +839,20 @@ void launch_cfg(const GemmArgs& a, hipStream_t st)
 
 template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
 {
-    // 256 x 256 tile, 8 waves of 128 x 64, 64-deep blocks, 2 ring slots.  (32-deep blocks in 4 slots bring the main
-    // loop 10 % closer to its pace without cache misses but lengthen everything around it: no gain on the whole.
-    // Two workgroups of 4 waves per compute unit, each on a 256 x 128 tile with 32-deep blocks, so that one computes
-    // while the other waits or writes its tile, are 15-20 % slower: they move half as much again into LDS per flop,
-    // and it is that traffic, not the latency of a request, that sets the pace.)
+    // 256 x 256 tile, 8 waves of 128 x 64, and a 128 KB ring: two slots of 64-deep blocks, or four slots of 32-deep
+    // blocks.  The finer ring keeps three quarters of itself in flight instead of half, which hides more of the
+    // operands' latency, at the price of twice as many barriers; measured, it is 5 % faster for the weight gradients
+    // and for FC2, even for FC1 and dXs, and 10 % slower for dH, so each kind gets its better one.
+    // (Two workgroups of 4 waves per compute unit, each on a 256 x 128 tile with 32-deep blocks, so that one computes
+    // while the other waits or writes its tile, are 15-20 % slower: they move half as much again into LDS per flop.)
     // Many small experts (fewer than 96 rows on average): 64 x 256 tiles, 8 waves of 64 x 32, 3 ring slots, so that a
     // tile is not mostly rows that do not exist.  (The weight gradients keep the large tile: their tile spans the
     // weight matrix, not the expert's rows.)
     if constexpr (KIND != kColsT) {
         if (a.M < 96L * a.E) { launch_cfg<KIND, 1, 8, 2, 1, 3, 64>(a, st); return; }
     }
-    launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st);
+    if constexpr (KIND == kColsT || KIND == kRowsNN) launch_cfg<KIND, 2, 4, 4, 2, 4, 32>(a, st);
+    else launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st);
 }
 }  // namespace sk
 
