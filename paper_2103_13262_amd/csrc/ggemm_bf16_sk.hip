@@ -57,8 +57,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef unsigned short u16;
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-constexpr int kMinSplitBlocks = 16;             // a stream-K piece is at least this many (full-cost) reduction blocks: handing a partial sum
-                                                // on costs about as much time as 6 blocks, and the hand-overs of one tile form a chain
+constexpr int kMinSplitDepth = 16 * 64;         // a stream-K piece is at least this deep (16 blocks of 64): handing a partial sum on costs
+                                                // about as much time as 6 such blocks, and the hand-overs of one tile form a chain
 constexpr int kActLo = (127 - 11) << 7;         // bf16 bit pattern of 2^-11
 constexpr int kActHi = (127 + 3) << 7;          // bf16 bit pattern of 2^3
 constexpr int kActEntries = kActHi - kActLo;    // table entries per sign
@@ -264,6 +264,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     };
     if constexpr (KIND != kColsT) {
         if (rem) {
+            constexpr int kMinSplitBlocks = kMinSplitDepth / BK;
             if (nkT >= 2 * kMinSplitBlocks) {
                 // long reductions: the left-over tiles' blocks, laid end to end, in equal contiguous ranges.  (Ranges
                 // of equal estimated time instead - blocks of tiles with few valid rows are cheaper - change nothing
