@@ -19,11 +19,16 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
+# Per-source flags.  The gate kernels carry their fp64 accumulators through loops; with the accumulators of the
+# matrix instructions in the separate accumulator registers the compiler copies them to and from the ordinary
+# registers around every loop iteration (and drains the matrix pipeline to do it), so for this file the matrix
+# instructions are told to accumulate in ordinary registers.
+SOURCE_FLAGS = {"gate_topk.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _compile(src, extra):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *SOURCE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the packed-fp32 feature name; that warning is harmless
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)

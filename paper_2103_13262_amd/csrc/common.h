@@ -26,7 +26,7 @@ struct WsLayout {
     size_t hist;      // [nb][E] int32: per plan-chunk histogram, then exclusive base inside the expert
     size_t dwg_part;  // [pieces][d] float: partial sums of dWg over pieces of 64 rows
     size_t dbg_part;  // [pieces] float
-    size_t WgT;       // [E][d] gate matrix transposed (written by the backward pass), element type = desc.dtype
+    size_t WgT;       // [E][d] gate matrix transposed (written by the plan step for E > 32 and by the backward pass), element type = desc.dtype
     size_t zeros;     // 1 KB of zeros (written by the plan step): source of masked reduction rows
     size_t sk_flags;  // [kMaxPersistentWgs] int32, directly behind the zero page and zeroed with it: "partial sum ready"
     size_t sk_error;  // int32 behind the flags, zeroed with them: set if a wait for a partial sum ran out
@@ -76,7 +76,7 @@ moe_status_t check_launch(const char* what);
 
 // ---- kernel launchers (each enqueues on `st`; operand shapes are validated by the callers) ----
 void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
-                      float* topk_w, hipStream_t st);
+                      float* topk_w, void* WgT, hipStream_t st);   // WgT: [E][d] scratch for the transposed gate matrix
 void launch_plan(const moe_desc_t& D, const WsLayout& L, const int32_t* topk_idx, int32_t* counts,
                  int32_t* offsets, int32_t* pos, int32_t* perm, char* ws, hipStream_t st);
 

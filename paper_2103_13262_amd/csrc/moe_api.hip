@@ -220,7 +220,7 @@ moe_status_t moe_plan(const moe_desc_t* desc, const void* X, const void* Wg, con
     const moe_desc_t& D = *desc;
     if (D.N > 0) {
         ScopedTimer tm(S_GATE, st);
-        launch_gate_topk(D, X, Wg, bg, plan->topk_idx, plan->topk_w, st);
+        launch_gate_topk(D, X, Wg, bg, plan->topk_idx, plan->topk_w, (char*)workspace + L.WgT, st);
         if ((s = check_launch("gate/top-k")) != MOE_OK) return s;
     }
     // With N == 0 the plan kernels still run: they write counts = 0, offsets = 0 and empty tile tables.

@@ -26,6 +26,11 @@ CASES = [
     Workload("single_token_bf16", 1, 64, 96, 3, 2, "bf16", 0.0, 17),
     Workload("top8_f32", 33, 32, 32, 9, 8, "f32", 0.0, 18),
     Workload("gate_over_256_experts_bf16", 200, 64, 32, 300, 3, "bf16", 0.0, 19),
+    # more than 32 experts with a feature count that ends in a partial slab of the gate kernel (bf16: 256 + 32,
+    # fp32: 128 + 32 features), and 17..32 experts
+    Workload("wide_gate_slabs_bf16", 300, 288, 64, 100, 2, "bf16", 0.0, 24),
+    Workload("wide_gate_slabs_f32", 150, 160, 64, 70, 3, "f32", 0.0, 25),
+    Workload("gate_24_experts_f32", 130, 96, 64, 24, 2, "f32", 0.0, 26),
     # few output tiles with a deep reduction: the tiles of the second and fourth grouped product are cut into
     # pieces of their reduction; in the first case a workgroup ends one tile and begins the next
     Workload("split_reduction_bf16", 360, 64, 384, 12, 2, "bf16", 0.0, 22),
