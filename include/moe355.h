@@ -30,6 +30,10 @@
  * the thread-local error string.  All work is enqueued on `stream` (a hipStream_t
  * passed as void*, NULL = the null stream); no call synchronises with the host or
  * copies anything to the host.  Calls return a status; nothing throws or aborts.
+ * The calls enqueue kernels only (no memset or copy nodes), so a sequence of them
+ * may be captured in a HIP graph once each has run once on the device outside a
+ * capture (the first launch of some kernels sets a function attribute); replays
+ * give the bits of the eager run (while per-kernel timing is off: moe_profile_*).
  */
 #ifndef MOE355_H
 #define MOE355_H

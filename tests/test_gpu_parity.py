@@ -206,3 +206,35 @@ def test_gpu_call_with_small_workspace_is_rejected():
     with pytest.raises(B.MoeError) as ei:
         B.moe_plan(run.desc, run.X, run.Wg, run.bg, b.plan, b.workspace, b.ws_bytes - 1, b.stream())
     assert ei.value.status == B.MOE_ERR_WORKSPACE
+
+
+def test_step_captured_in_a_graph_replays_bit_for_bit():
+    """The three calls enqueue kernels only (no host synchronisation, no memset nodes, no allocation after
+    the first call), so a caller may capture them in a HIP graph: every replay, with eager work in between,
+    must give the bits of the eager run."""
+    import torch
+
+    w = Workload("graph", 1100, 128, 1024, 9, 2, "bf16", 0.9, 71)     # whole tiles, split reductions, ragged tails
+    inp = make_inputs(w)
+    run = GpuRun(w, inp).run()                                          # eager; also the kernels' first launches
+    outs = ("Y", "dX", "dW1", "dW2", "dWg", "dbg")
+    bits = lambda t: t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32)
+    ref = {n: bits(getattr(run, n)).clone() for n in outs}
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run.plan()
+            run.forward()
+            run.backward()
+    for replay in range(3):
+        for n in outs:
+            getattr(run, n).fill_(float("nan"))
+        other = GpuRun(Workload("between", 300, 64, 96, 5, 2, "bf16", 0.0, 72 + replay),
+                       make_inputs(Workload("between", 300, 64, 96, 5, 2, "bf16", 0.0, 72 + replay))).run()
+        assert other.status() == 0
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in outs:
+            assert torch.equal(bits(getattr(run, n)), ref[n]), (replay, n)
+    assert run.status() == 0
