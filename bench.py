@@ -39,6 +39,10 @@ def parse():
                     help="throughput of the grouped matrix products against the batch an expert sees (the paper's "
                          "Section 4 figure of GeMM throughput against problem size): token counts at d_m=1024, "
                          "d_h=4096, 16 experts, k=2, i.e. N/8 rows per expert; one JSON line per count")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="context only: the rate of the vendor library's dense bf16 product (torch.matmul) on the six "
+                         "product shapes of the workload with equal experts, i.e. what a tuned plain GEMM reaches on "
+                         "this machine where the grouped kernel reaches roofline.achieved; one JSON line per shape")
     return ap.parse_args()
 
 
@@ -103,6 +107,26 @@ def main():
                               "tokens_per_s": out["value"], "grouped_gemm_tflops": out["roofline"]["achieved"],
                               "grouped_gemm_avg_launch_us": out["roofline"]["avg_launch_us"]}), flush=True)
             torch.cuda.empty_cache()
+        return
+    if a.library_gemm:
+        w = WORKLOADS[a.workload]
+        M = w.N * w.k
+        # (rows, columns, reduction) of FC1 / dH, FC2 / dXs and of the two weight gradients taken over all rows at once
+        for name, (m, n, kk) in (("fc1", (M, w.h, w.d)), ("fc2", (M, w.d, w.h)), ("dw1_all_rows", (w.d, w.h, M)),
+                                 ("dw2_all_rows", (w.h, w.d, M))):
+            x = torch.randn(m, kk, device="cuda:0", dtype=torch.bfloat16)
+            y = torch.randn(kk, n, device="cuda:0", dtype=torch.bfloat16)
+            for _ in range(a.warmup):
+                x @ y
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(a.steps):
+                x @ y
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / a.steps * 1e3
+            print(json.dumps({"library_gemm": name, "workload": w.name, "m": m, "n": n, "k": kk, "us": us,
+                              "tflops": 2.0 * m * n * kk / us / 1e6}), flush=True)
         return
     print(json.dumps(run(a, torch, B, WORKLOADS, make_inputs)))
 
