@@ -64,10 +64,18 @@ __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ hist, in
     const int e = threadIdx.x;
     int cnt = 0;
     if (e < E) {
-        for (int b = 0; b < nb; ++b) {
-            const int v = hist[(size_t)b * E + e];
-            hist[(size_t)b * E + e] = cnt;
-            cnt += v;
+        // chunk histograms -> exclusive bases inside the expert, eight chunks at a time so that their loads are in
+        // flight together (one after the other, each load would wait for the store before it)
+        for (int b0 = 0; b0 < nb; b0 += 8) {
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = hist[(size_t)min(b0 + u, nb - 1) * E + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (b0 + u < nb) {
+                    hist[(size_t)(b0 + u) * E + e] = cnt;
+                    cnt += v[u];
+                }
         }
         counts[e] = cnt;
     }
@@ -84,8 +92,8 @@ __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ hist, in
         if (e == 0) tileP[q * (E + 1) + E] = total;
     }
     __syncthreads();
+    int rank = 0;                         // experts by descending count, ties by ascending id
     if (e < E) {
-        int rank = 0;
         for (int o = 0; o < E; ++o) {
             const int c = s_cnt[o];
             rank += (c > cnt || (c == cnt && o < e)) ? 1 : 0;
@@ -98,14 +106,7 @@ __global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ hist, in
     __shared__ int s_xcd[8];
     if (threadIdx.x < 8) s_xcd[threadIdx.x] = 0;
     __syncthreads();
-    if (e < E) {
-        int rank = 0;
-        for (int o = 0; o < E; ++o) {
-            const int c = s_cnt[o];
-            rank += (c > cnt || (c == cnt && o < e)) ? 1 : 0;
-        }
-        atomicAdd(&s_xcd[(rank >> 3) & 1 ? 7 - (rank & 7) : rank & 7], (cnt + 63) / 64);
-    }
+    if (e < E) atomicAdd(&s_xcd[(rank >> 3) & 1 ? 7 - (rank & 7) : rank & 7], (cnt + 63) / 64);
     __syncthreads();
     if (threadIdx.x == 0) {
         int mx = 0, sum = 0;

@@ -244,16 +244,25 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
     }
 }
 
+// grid (ceil(d / 256), E): a thread owns one row of one expert's column, so that the threads of a wavefront read
+// consecutive floats of every piece; the pieces are added in ascending order (loads four at a time, sums in order).
 template <typename G>
 __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part, const float* __restrict__ bpart,
                                                  const int32_t* __restrict__ P64, G* __restrict__ dWg,
                                                  float* __restrict__ dbg, int d, int E, int accumulate)
 {
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;  // i = row * E + e of dWg
-    if (i < (long)d * E) {
-        const int row = (int)(i / E), e = (int)(i % E);
+    const int row = blockIdx.x * 256 + threadIdx.x, e = blockIdx.y;
+    const int q1 = P64[e + 1];
+    if (row < d) {
         float s = 0.f;
-        for (int q = P64[e]; q < P64[e + 1]; ++q) s += part[(size_t)q * d + row];
+        int q = P64[e];
+        for (; q + 4 <= q1; q += 4) {
+            const float a0 = part[(size_t)q * d + row], a1 = part[(size_t)(q + 1) * d + row];
+            const float a2 = part[(size_t)(q + 2) * d + row], a3 = part[(size_t)(q + 3) * d + row];
+            s = (((s + a0) + a1) + a2) + a3;
+        }
+        for (; q < q1; ++q) s += part[(size_t)q * d + row];
+        const size_t i = (size_t)row * E + e;
         if constexpr (sizeof(G) == 2) {
             if (accumulate) s += bf16_to_f32(dWg[i]);
             dWg[i] = f32_to_bf16(s);
@@ -262,11 +271,11 @@ __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part,
             dWg[i] = s;
         }
     }
-    if (dbg && i < E) {
+    if (dbg && row == 0) {
         float s = 0.f;
-        for (int q = P64[i]; q < P64[i + 1]; ++q) s += bpart[q];
-        if (accumulate) s += dbg[i];
-        dbg[i] = s;
+        for (int q = P64[e]; q < q1; ++q) s += bpart[q];
+        if (accumulate) s += dbg[e];
+        dbg[e] = s;
     }
 }
 
@@ -321,7 +330,7 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     float* bpart = (float*)(ws + L.dbg_part);
     const int32_t* P64 = (const int32_t*)(ws + L.tileP) + tile_height_index(64) * (D.E + 1);
     const dim3 pg((unsigned)L.dwg_pieces, (cpr + 127) / 128);
-    const unsigned fg = (unsigned)(((long)D.d * D.E + 255) / 256);
+    const dim3 fg((unsigned)((D.d + 255) / 256), (unsigned)D.E);
     const unsigned xg = grid_for((long)D.N * cpr);
     const unsigned tg = (unsigned)(((long)D.d * D.E + 255) / 256);
     void* WgT = ws + L.WgT;
@@ -330,10 +339,10 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
         hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
         hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
         if (D.grad_dtype == MOE_BF16)
-            hipLaunchKernelGGL(dwg_final<unsigned short>, dim3(fg), dim3(256), 0, st, (const float*)part,
+            hipLaunchKernelGGL(dwg_final<unsigned short>, fg, dim3(256), 0, st, (const float*)part,
                                (const float*)bpart, P64, (unsigned short*)dWg, dbg, D.d, D.E, D.accumulate);
         else
-            hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
+            hipLaunchKernelGGL(dwg_final<float>, fg, dim3(256), 0, st, (const float*)part, (const float*)bpart,
                                P64, (float*)dWg, dbg, D.d, D.E, D.accumulate);
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
                            (long)D.N, D.k, cpr);
@@ -341,7 +350,7 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
         using T = float;
         hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
         hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
-        hipLaunchKernelGGL(dwg_final<float>, dim3(fg), dim3(256), 0, st, (const float*)part, (const float*)bpart,
+        hipLaunchKernelGGL(dwg_final<float>, fg, dim3(256), 0, st, (const float*)part, (const float*)bpart,
                            P64, (float*)dWg, dbg, D.d, D.E, D.accumulate);
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
                            (long)D.N, D.k, cpr);
