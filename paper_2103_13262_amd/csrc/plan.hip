@@ -2,7 +2,8 @@
 // (Section 3.2: the samples per expert are counted first and the buffer offsets follow from
 // the counts; Section 4: the samples of one expert lie contiguously).  Integer work only.
 //
-//   plan_hist : per chunk of kPlanChunk assignments, an LDS histogram over experts.
+//   plan_hist : per chunk of kPlanChunk assignments, an LDS histogram over experts (small problems: done by
+//               plan_scan itself, which saves the launch).
 //   plan_scan : one workgroup; column scan over chunks -> counts and per-chunk bases, exclusive
 //               scan over experts -> offsets, tile prefix tables for four row-tile heights,
 //               experts ordered by descending count.
@@ -52,18 +53,48 @@ __device__ __forceinline__ int block_excl_scan_1024(int v, int* s_wave /*[16]*/,
     return wbase + inc - v;
 }
 
-__global__ __launch_bounds__(1024) void plan_scan(int32_t* __restrict__ hist, int nb, int E, long M,
-                                                  int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-                                                  int32_t* __restrict__ tileP, int32_t* __restrict__ order,
-                                                  int32_t* __restrict__ zeros)
+constexpr int kFusedHistInts = 8192;   // chunk histograms that plan_scan builds itself when they fit (32 KB of LDS)
+
+// idx == nullptr: the chunk histograms were written to `hist` by plan_hist.  Otherwise (nb * E <= kFusedHistInts)
+// this workgroup counts the assignments itself, into LDS, and saves that launch.
+__global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ idx, int32_t* __restrict__ hist, int nb,
+                                                  int E, long M, int32_t* __restrict__ counts,
+                                                  int32_t* __restrict__ offsets, int32_t* __restrict__ tileP,
+                                                  int32_t* __restrict__ order, int32_t* __restrict__ zeros)
 {
     // page read in place of masked rows, and the flags of the persistent matrix-product kernels behind it
     if (threadIdx.x < (int)(kZeroedBytes / 4)) zeros[threadIdx.x] = 0;
     __shared__ int s_cnt[kMaxE];
     __shared__ int s_wave[16];
+    __shared__ int s_hist[kFusedHistInts];
     const int e = threadIdx.x;
     int cnt = 0;
-    if (e < E) {
+    if (idx) {
+        for (int i = threadIdx.x; i < nb * E; i += 1024) s_hist[i] = 0;
+        __syncthreads();
+        for (long a0 = 0; a0 < M; a0 += 8 * 1024) {       // eight loads in flight per thread
+            int ev[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const long a = a0 + u * 1024 + threadIdx.x;
+                ev[u] = a < M ? idx[a] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const long a = a0 + u * 1024 + threadIdx.x;
+                if (ev[u] >= 0 && ev[u] < E) atomicAdd(&s_hist[(int)(a / kPlanChunk) * E + ev[u]], 1);
+            }
+        }
+        __syncthreads();
+        if (e < E) {
+            for (int b = 0; b < nb; ++b) {                // exclusive bases inside the expert, for plan_rank
+                const int v = s_hist[b * E + e];
+                hist[(size_t)b * E + e] = cnt;
+                cnt += v;
+            }
+            counts[e] = cnt;
+        }
+    } else if (e < E) {
         // chunk histograms -> exclusive bases inside the expert, eight chunks at a time so that their loads are in
         // flight together (one after the other, each load would wait for the store before it)
         for (int b0 = 0; b0 < nb; b0 += 8) {
@@ -178,9 +209,10 @@ void launch_plan(const moe_desc_t& D, const WsLayout& L, const int32_t* topk_idx
     int32_t* order = (int32_t*)(ws + L.order);
     int nbits = 0;
     while ((1 << nbits) < D.E) ++nbits;
-    if (L.nb > 0) hipLaunchKernelGGL(plan_hist, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, hist);
-    hipLaunchKernelGGL(plan_scan, dim3(1), dim3(1024), 0, st, hist, L.nb, D.E, M, counts, offsets, tileP, order,
-                       (int32_t*)(ws + L.zeros));
+    const bool fused = L.nb > 0 && (long)L.nb * D.E <= kFusedHistInts;
+    if (L.nb > 0 && !fused) hipLaunchKernelGGL(plan_hist, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, hist);
+    hipLaunchKernelGGL(plan_scan, dim3(1), dim3(1024), 0, st, fused ? topk_idx : (const int32_t*)nullptr, hist, L.nb, D.E,
+                       M, counts, offsets, tileP, order, (int32_t*)(ws + L.zeros));
     if (L.nb > 0)
         hipLaunchKernelGGL(plan_rank, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, nbits, (const int32_t*)hist,
                            (const int32_t*)offsets, pos, perm);
