@@ -18,7 +18,8 @@
  *   - ArgMax_k ranks the raw logits; equal logits go to the lower expert id;
  *     slot j holds the j-th largest.
  *   - score_i is the softmax over the k selected logits (weights sum to 1).
- *   - the expert is W2^T GeLU(W1^T x) with the exact erf GeLU, no biases.
+ *   - the expert is W2^T GeLU(W1^T x + b1) + b2 with the exact erf GeLU; the
+ *     biases are optional (the paper's expert is "an FFN": two linear layers).
  *   - inside an expert's contiguous segment rows keep assignment order
  *     a = t*k + j (a stable counting sort).
  *   - the backward is the ordinary gradient of L = <dY, Y> with the top-k
@@ -52,6 +53,8 @@ typedef struct {
     const void *W1;       /* [E, d, h]                                            */
     const void *W2;       /* [E, h, d]                                            */
     const void *dY;       /* [N, d] or NULL (forward only)                        */
+    const double *b1;     /* [E, h] expert biases of the first layer, or NULL     */
+    const double *b2;     /* [E, d] expert biases of the second layer, or NULL    */
 } orc_problem;
 
 static inline double ld(const void *p, int dtype, size_t i)
@@ -163,12 +166,13 @@ int orc_plan(int64_t M, int32_t E, const int32_t *idx /*[M]*/, int32_t *counts /
  *   idx[n_tok,k], w[n_tok,k], dl[n_tok,k]
  *   Zo[n_tok,k,h] pre-activation, Oo[n_tok,k,d] expert outputs E_i(x)
  *   dW1[n_track,d,h], dW2[n_track,h,d] accumulated over the listed tokens (zeroed here)
+ *   db1[n_track,h], db2[n_track,d]    likewise, gradients of the expert biases
  *   dWg[d,E], dbg[E]                  accumulated over the listed tokens (zeroed here)
  */
 int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const int32_t *track,
               int32_t n_track, int32_t only_tracked, double *Y, double *dX, int32_t *idx_out,
               double *w_out, double *dl_out, double *Zo, double *Oo, double *dW1, double *dW2,
-              double *dWg, double *dbg)
+              double *dWg, double *dbg, double *db1, double *db2)
 {
     const int d = p->d, h = p->h, E = p->E, k = p->k, dt = p->dtype;
     if (k < 1 || k > E) return -1;
@@ -193,6 +197,8 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
     const size_t dh = (size_t)d * h;
     if (dW1) memset(dW1, 0, sizeof(double) * dh * (size_t)nslots);
     if (dW2) memset(dW2, 0, sizeof(double) * dh * (size_t)nslots);
+    if (db1) memset(db1, 0, sizeof(double) * (size_t)h * (size_t)nslots);
+    if (db2) memset(db2, 0, sizeof(double) * (size_t)d * (size_t)nslots);
     if (dWg) memset(dWg, 0, sizeof(double) * (size_t)d * E);
     if (dbg) memset(dbg, 0, sizeof(double) * (size_t)E);
 
@@ -232,6 +238,7 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
             for (int c = 0; c < h; ++c) {
                 double s = 0.0;
                 for (int i = 0; i < d; ++i) s += x[i] * ld(p->W1, dt, w1o + (size_t)i * h + c);
+                if (p->b1) s += p->b1[(size_t)e * h + c];
                 zj[c] = s;
                 gj[c] = gelu(s);
             }
@@ -239,6 +246,7 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
             for (int i = 0; i < d; ++i) {
                 double s = 0.0;
                 for (int c = 0; c < h; ++c) s += gj[c] * ld(p->W2, dt, w2o + (size_t)c * d + i);
+                if (p->b2) s += p->b2[(size_t)e * d + i];
                 oj[i] = s;
             }
             for (int i = 0; i < d; ++i) y[i] = w[j] * oj[i] + y[i];
@@ -280,6 +288,8 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
             const size_t w1o = (size_t)e * dh, w2o = (size_t)e * dh;
             const double *zj = z + (size_t)j * h, *gj = g + (size_t)j * h;
             for (int i = 0; i < d; ++i) dout[i] = w[j] * dy[i];       /* dL/do_j */
+            if (db2 && s >= 0)                                        /* o = ... + b2 */
+                for (int i = 0; i < d; ++i) db2[(size_t)s * d + i] += dout[i];
             /* o = W2^T g : dg = W2 dout ; dW2 += g (x) dout */
 #pragma omp parallel for schedule(static)
             for (int c = 0; c < h; ++c) {
@@ -291,6 +301,8 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
                     for (int i = 0; i < d; ++i) row[i] += gj[c] * dout[i];
                 }
             }
+            if (db1 && s >= 0)                                        /* z = ... + b1 */
+                for (int c = 0; c < h; ++c) db1[(size_t)s * h + c] += dz[c];
             /* z = W1^T x : dW1 += x (x) dz ; dx += W1 dz */
 #pragma omp parallel for schedule(static)
             for (int i = 0; i < d; ++i) {

@@ -21,6 +21,7 @@ class _Problem(C.Structure):
         ("dtype", C.c_int32),
         ("X", C.c_void_p), ("Wg", C.c_void_p), ("bg", C.c_void_p),
         ("W1", C.c_void_p), ("W2", C.c_void_p), ("dY", C.c_void_p),
+        ("b1", C.c_void_p), ("b2", C.c_void_p),
     ]
 
 
@@ -58,9 +59,9 @@ def bf16_bits_to_f64(a):
 
 
 class OracleProblem:
-    """X[N,d], Wg[d,E], W1[E,d,h], W2[E,h,d], optional bg[E] (float64), optional dY[N,d]."""
+    """X[N,d], Wg[d,E], W1[E,d,h], W2[E,h,d], optional bg[E], b1[E,h], b2[E,d] (float64), optional dY[N,d]."""
 
-    def __init__(self, X, Wg, W1, W2, k, bg=None, dY=None):
+    def __init__(self, X, Wg, W1, W2, k, bg=None, dY=None, b1=None, b2=None):
         arrs = [np.ascontiguousarray(a) for a in (X, Wg, W1, W2)]
         self.X, self.Wg, self.W1, self.W2 = arrs
         self.dY = None if dY is None else np.ascontiguousarray(dY)
@@ -75,9 +76,13 @@ class OracleProblem:
         assert self.Wg.shape == (self.d, self.E)
         assert self.bg is None or self.bg.shape == (self.E,)
         assert self.dY is None or self.dY.shape == self.X.shape
+        self.b1 = None if b1 is None else np.ascontiguousarray(b1, dtype=np.float64)
+        self.b2 = None if b2 is None else np.ascontiguousarray(b2, dtype=np.float64)
+        assert self.b1 is None or self.b1.shape == (self.E, self.h)
+        assert self.b2 is None or self.b2.shape == (self.E, self.d)
         self.k = int(k)
         self._c = _Problem(self.N, self.d, self.h, self.E, self.k, code, _ptr(self.X), _ptr(self.Wg),
-                           _ptr(self.bg), _ptr(self.W1), _ptr(self.W2), _ptr(self.dY))
+                           _ptr(self.bg), _ptr(self.W1), _ptr(self.W2), _ptr(self.dY), _ptr(self.b1), _ptr(self.b2))
 
 
 def num_threads():
@@ -146,9 +151,12 @@ def layer(p: OracleProblem, tokens=None, track=None, only_tracked=False, want_in
     dW2 = alloc("dW2", (nslots, p.h, p.d), backward and want_dw)
     dWg = alloc("dWg", (p.d, p.E), full and backward)
     dbg = alloc("dbg", (p.E,), full and backward)
+    db1 = alloc("db1", (nslots, p.h), backward and want_dw)
+    db2 = alloc("db2", (nslots, p.d), backward and want_dw)
     rc = _load().orc_layer(C.byref(p._c), _ptr(tokens), C.c_int32(nt), _ptr(trk), C.c_int32(ntrk),
                            C.c_int32(1 if only_tracked else 0), _ptr(Y), _ptr(dX), _ptr(idx), _ptr(w),
-                           _ptr(dl), _ptr(Z), _ptr(O), _ptr(dW1), _ptr(dW2), _ptr(dWg), _ptr(dbg))
+                           _ptr(dl), _ptr(Z), _ptr(O), _ptr(dW1), _ptr(dW2), _ptr(dWg), _ptr(dbg), _ptr(db1),
+                           _ptr(db2))
     if rc:
         raise ValueError(f"orc_layer failed ({rc})")
     out["tokens"] = tokens

@@ -101,6 +101,46 @@ def test_single_expert_is_dense_ffn_forward_and_backward():
     assert np.all(out["dl"] == 0.0) and np.all(out["dWg"] == 0.0) and np.all(out["dbg"] == 0.0)
 
 
+def test_single_expert_with_biases_is_dense_ffn_with_biases():
+    # E = 1, k = 1: Y = GeLU(X W1 + b1) W2 + b2, and the textbook gradients of that dense network
+    p0 = _rand_problem(21, N=9, d=5, h=7, E=1, k=1)
+    g = np.random.default_rng(21)
+    b1, b2 = g.standard_normal((1, 7)), g.standard_normal((1, 5))
+    p = orc.OracleProblem(p0.X, p0.Wg, p0.W1, p0.W2, 1, bg=p0.bg, dY=p0.dY, b1=b1, b2=b2)
+    out = orc.layer(p)
+    X, W1, W2, dY = p.X, p.W1[0], p.W2[0], p.dY
+    Z = X @ W1 + b1[0]
+    G = _gelu(Z)
+    np.testing.assert_allclose(out["Y"], G @ W2 + b2[0], rtol=1e-12, atol=1e-13)
+    dZ = (dY @ W2.T) * _gelu_grad(Z)
+    np.testing.assert_allclose(out["dW2"][0], G.T @ dY, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out["dW1"][0], X.T @ dZ, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out["dX"], dZ @ W1.T, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out["db2"][0], dY.sum(0), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out["db1"][0], dZ.sum(0), rtol=1e-12, atol=1e-12)
+
+
+def test_zero_biases_change_nothing_and_b2_shifts_the_output_by_the_weighted_biases():
+    p0 = _rand_problem(22, N=7, d=4, h=6, E=4, k=2)
+    base = orc.layer(p0)
+    z = orc.layer(orc.OracleProblem(p0.X, p0.Wg, p0.W1, p0.W2, 2, bg=p0.bg, dY=p0.dY, b1=np.zeros((4, 6)),
+                                    b2=np.zeros((4, 4))))
+    for n in ("Y", "dX", "dW1", "dW2", "dWg", "dbg"):
+        np.testing.assert_array_equal(z[n], base[n])
+    # Y is affine in b2: Y(b2) - Y(0) = sum_j w_j b2[idx_j]  (Algorithm 1's weighted sum)
+    b2 = np.random.default_rng(22).standard_normal((4, 4))
+    out = orc.layer(orc.OracleProblem(p0.X, p0.Wg, p0.W1, p0.W2, 2, bg=p0.bg, b2=b2))
+    shift = (base["w"][:, :, None] * b2[base["idx"]]).sum(1)
+    np.testing.assert_allclose(out["Y"] - base["Y"], shift, rtol=1e-11, atol=1e-13)
+    # each expert's db2 is the sum of w_j dY over the slots routed to it; db1, db2 rows of unused experts are zero
+    ob = orc.layer(orc.OracleProblem(p0.X, p0.Wg, p0.W1, p0.W2, 2, bg=p0.bg, dY=p0.dY, b2=b2))
+    ref = np.zeros((4, 4))
+    for t in range(7):
+        for j in range(2):
+            ref[base["idx"][t, j]] += base["w"][t, j] * p0.dY[t]
+    np.testing.assert_allclose(ob["db2"], ref, rtol=1e-12, atol=1e-13)
+
+
 def test_k_equals_E_is_dense_softmax_mixture():
     p = _rand_problem(2, N=6, d=4, h=5, E=3, k=3, dy=False)
     out = orc.layer(p)
@@ -208,7 +248,7 @@ def test_plan_rejects_out_of_range_expert():
 
 # ------------------------------------------------------------------ (d) gradients by finite differences
 def _loss(p):
-    return float((orc.layer(orc.OracleProblem(p.X, p.Wg, p.W1, p.W2, p.k, bg=p.bg))["Y"] * p.dY).sum())
+    return float((orc.layer(orc.OracleProblem(p.X, p.Wg, p.W1, p.W2, p.k, bg=p.bg, b1=p.b1, b2=p.b2))["Y"] * p.dY).sum())
 
 
 @pytest.mark.parametrize("k,E", [(2, 4), (1, 3), (3, 3)])
@@ -221,10 +261,13 @@ def test_gradients_match_central_differences(k, E):
             break
     else:
         pytest.skip("no seed with a safe decision gap")
+    g = np.random.default_rng(k * 10 + E)
+    p = orc.OracleProblem(p.X, p.Wg, p.W1, p.W2, p.k, bg=p.bg, dY=p.dY, b1=0.3 * g.standard_normal((E, 5)),
+                          b2=0.3 * g.standard_normal((E, 3)))
     out = orc.layer(p)
     eps = 1e-6
     for name, grad in (("X", out["dX"]), ("Wg", out["dWg"]), ("bg", out["dbg"]),
-                       ("W1", out["dW1"]), ("W2", out["dW2"])):
+                       ("W1", out["dW1"]), ("W2", out["dW2"]), ("b1", out["db1"]), ("b2", out["db2"])):
         arr = getattr(p, name)
         num = np.zeros_like(arr)
         it = np.nditer(arr, flags=["multi_index"])
