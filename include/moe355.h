@@ -19,7 +19,7 @@
  * Points on which the paper is silent and this library fixes a reading:
  *   logits l = x W_g + b_g;  top-k on the logits, equal logits -> lower expert id,
  *   slot j = j-th largest;  score = softmax over the k selected logits;
- *   E_e(x) = GeLU(x W1[e]) W2[e] with the erf GeLU and no expert biases;
+ *   E_e(x) = GeLU(x W1[e] + b1[e]) W2[e] + b2[e] with the erf GeLU (the biases are optional);
  *   inside an expert's segment rows keep assignment order a = t*k + j;
  *   backward = gradient of <dY, Y> with the selected indices held constant.
  *
@@ -104,7 +104,9 @@ moe_status_t moe_plan(const moe_desc_t *desc, const void *X, const void *Wg, con
 /*
  * Forward: scatter, per-expert FFN as grouped matrix products, weighted gather
  * (Section 4 reordering of Algorithm 1's loop).
- *   W1 device [E,d,h], W2 device [E,h,d] dtype;  b1, b2 must be NULL (expert biases unsupported).
+ *   W1 device [E,d,h], W2 device [E,h,d] dtype.
+ *   b1 device [E,h], b2 device [E,d] dtype, or NULL: the biases of the expert's two linear
+ *   layers (the paper's expert is an FFN, Section 5.1): E_e(x) = GeLU(x W1[e] + b1[e]) W2[e] + b2[e].
  *   Y device [N,d] dtype, written.
  * Leaves Xs, Z (pre-activation), H and Ys in the workspace for moe_backward.  bf16: Z is the
  * rounded accumulator, H = z * Phi(Z) with z the fp32 accumulator and Phi the normal CDF taken at
@@ -127,6 +129,18 @@ moe_status_t moe_forward(const moe_desc_t *desc, const moe_plan_t *plan, const v
 moe_status_t moe_backward(const moe_desc_t *desc, const moe_plan_t *plan, const void *X, const void *Wg,
                           const void *W1, const void *W2, const void *dY, void *dX, void *dWg, float *dbg,
                           void *dW1, void *dW2, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Gradients of the expert biases (only needed when moe_forward was given b1 / b2; the other
+ * gradients do not change form with biases, since Z is stored with b1 included).  Must follow
+ * moe_backward on the same desc, plan and untouched workspace: per expert it sums, in a fixed
+ * order, the rows of dZ (db1) and of the weighted output gradients dYs (db2) that moe_backward
+ * left there.
+ *   db1 device [E,h] float or NULL, db2 device [E,d] float or NULL; written, or added to when
+ *   desc->accumulate is 1.  Rows of experts that received no token are zero (or unchanged).
+ */
+moe_status_t moe_bias_backward(const moe_desc_t *desc, const moe_plan_t *plan, float *db1, float *db2,
+                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * The data-movement steps on their own, so that any expert network can sit between them (the

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe355.so")
 MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP = 0, -1, -2, -3, -4
 MOE_F32, MOE_BF16 = 0, 1
 EXPORTS = ("moe_workspace_bytes", "moe_workspace_region", "moe_plan", "moe_forward", "moe_backward",
-           "moe_scatter", "moe_gather", "moe_gather_backward", "moe_scatter_backward",
+           "moe_bias_backward", "moe_scatter", "moe_gather", "moe_gather_backward", "moe_scatter_backward",
            "moe_last_error", "moe_profile_enable", "moe_profile_read")
 
 
@@ -145,6 +145,11 @@ def moe_backward(desc, plan, X, Wg, W1, W2, dY, dX, dWg, dbg, dW1, dW2, workspac
     _check(lib().moe_backward(C.byref(desc), C.byref(plan), _p(X), _p(Wg), _p(W1), _p(W2), _p(dY), _p(dX),
                               _p(dWg), _p(dbg), _p(dW1), _p(dW2), _p(workspace), C.c_size_t(workspace_bytes),
                               C.c_void_p(stream)))
+
+
+def moe_bias_backward(desc, plan, db1, db2, workspace, workspace_bytes, stream=0):
+    _check(lib().moe_bias_backward(C.byref(desc), None if plan is None else C.byref(plan), _p(db1), _p(db2), _p(workspace),
+                                   C.c_size_t(workspace_bytes), C.c_void_p(stream)))
 
 
 def moe_scatter(desc, plan, X, Xs, stream=0):

@@ -26,6 +26,7 @@ struct WsLayout {
     size_t hist;      // [nb][E] int32: per plan-chunk histogram, then exclusive base inside the expert
     size_t dwg_part;  // [pieces][d] float: partial sums of dWg over pieces of 64 rows
     size_t dbg_part;  // [pieces] float
+    size_t bias_part; // [pieces][max(d,h)] float: partial column sums for the expert-bias gradients
     size_t WgT;       // [E][d] gate matrix transposed (written by the plan step for E > 32 and by the backward pass), element type = desc.dtype
     size_t zeros;     // 1 KB of zeros (written by the plan step): source of masked reduction rows
     size_t sk_flags;  // [kMaxPersistentWgs] int32, directly behind the zero page and zeroed with it: "partial sum ready"
@@ -61,6 +62,7 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.dwg_pieces = (long)(M / 64) + D.E;
     L.dwg_part = take((size_t)L.dwg_pieces * D.d * sizeof(float));
     L.dbg_part = take((size_t)L.dwg_pieces * sizeof(float));
+    L.bias_part = take((size_t)L.dwg_pieces * (D.d > D.h ? D.d : D.h) * sizeof(float));
     L.WgT = take((size_t)D.E * D.d * b);
     L.zeros = take(kZeroedBytes);
     L.sk_flags = L.zeros + 1024;
@@ -107,6 +109,7 @@ struct GemmArgs {
     void* C;
     void* C2;         // kRowsNN_GeLU: GeLU output
     const void* Zin;  // kRowsNT_dGeLU: saved pre-activation [M,Nout]
+    const void* bias; // kRowsNN_GeLU, kRowsNN: [E,Nout] added to the product (activation type), or NULL
     int K;            // kRows*: reduction width;  kColsT: K1 (rows of C[e])
     int Nout;         // kRows*: columns of C;     kColsT: K2 (columns of C[e])
     long M;           // total rows (N*k)
@@ -125,6 +128,8 @@ struct GemmArgs {
     int accumulate;   // kColsT
     long long* trace; // development builds only: per-workgroup phase times (8 words per workgroup) or NULL
 };
+void launch_segment_sums(const moe_desc_t& D, const WsLayout& L, const void* src, int width, const int32_t* counts,
+                         const int32_t* offsets, float* out, char* ws, hipStream_t st);
 void launch_ggemm_f32(const GemmArgs& a, hipStream_t st);
 void launch_ggemm_bf16_sk(const GemmArgs& a, hipStream_t st);
 

@@ -162,10 +162,11 @@ struct Item {
     int Mt, Nt, Kt;       // valid rows / columns of the tile, reduction length
     int kb0, kb1;         // reduction blocks [kb0, kb1) of the tile
     int owner;            // the range holds the tile's last block: this workgroup writes the tile
+    size_t b_off;         // rows kinds: expert * Nout + first column (where the tile's bias values start)
 };
 
 struct Fin {              // what finishing an item needs once the streams have moved on to the next one
-    size_t c_off;
+    size_t c_off, b_off;
     int Mt, Nt, owner;
 };
 
@@ -260,6 +261,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         if constexpr (C::B_TRANS) { it.B = Be + n0; it.ldb = g.Nout; }
         else                      { it.B = Be + (size_t)n0 * g.K; it.ldb = g.K; }
         it.c_off = (size_t)r0 * g.Nout + n0;
+        it.b_off = (size_t)e * g.Nout + n0;
         it.Mt = min(rows_per, g.counts[e] - mt * BM - row_off);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.K;
     };
     if constexpr (KIND != kColsT) {
@@ -332,6 +334,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
             it.A = (const u16*)g.A + off * g.K + m0;     it.lda = g.K;
             it.B = (const u16*)g.B + off * g.Nout + n0;  it.ldb = g.Nout;
             it.c_off = ((size_t)e * g.K + m0) * g.Nout + n0;
+            it.b_off = 0;
             it.Mt = min(BM, g.K - m0);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.counts[e];
             it.kb0 = 0;  it.kb1 = (it.Kt + BK - 1) / BK;  it.owner = 1;
             return true;
@@ -627,6 +630,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
                     v.lo = *(const float4*)patch_r;
                     v.hi = *(const float4*)(patch_r + 4);
                 };
+                float bias[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // of this lane's 8 columns (the same for every row)
+                if constexpr (KIND == kRowsNN_GeLU || KIND == kRowsNN) {
+                    if (g.bias && pok) unpack8(*(const uint4*)((const u16*)g.bias + it.b_off + pcol), bias);
+                }
                 uint4 zin[4];
                 if constexpr (KIND == kRowsNT_dGeLU) {   // saved pre-activations of the whole block, requested up front
 #pragma unroll
@@ -659,6 +666,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
                     const int row = row0 + sl * 8 + prow;
                     if (pok && row < it.Mt) {
                         float x[8] = {cur.lo.x, cur.lo.y, cur.lo.z, cur.lo.w, cur.hi.x, cur.hi.y, cur.hi.z, cur.hi.w};
+                        if constexpr (KIND == kRowsNN_GeLU || KIND == kRowsNN) {
+#pragma unroll
+                            for (int t = 0; t < 8; ++t) x[t] += bias[t];
+                        }
                         const size_t o = it.c_off + (size_t)row * ldc + pcol;
                         if constexpr (KIND == kRowsNN_GeLU) {
                             const uint4 zp = pack8(x);
@@ -743,7 +754,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
             __builtin_amdgcn_s_barrier();              // every wave is done reading the ring
         }
         TRACE_PHASE(2);
-        const Fin fin{cur.c_off, cur.Mt, cur.Nt, cur.owner};
+        const Fin fin{cur.c_off, cur.b_off, cur.Mt, cur.Nt, cur.owner};
         if (cur.kb0 > 0) add_predecessor();   // the blocks before kb0 were summed by the workgroup just below
         have = next_item(cur);
         if (have) start_item(cur);

@@ -13,7 +13,7 @@ constexpr int TM = 64, TN = 64, TK = 16;
 struct TileF32 {
     const float* A; long sam, sak;   // A'(m,kk) = A[m*sam + kk*sak]
     const float* B; long sbk, sbn;   // B'(kk,n) = B[kk*sbk + n*sbn]
-    float* C; float* C2; const float* Z; long ldc;
+    float* C; float* C2; const float* Z; const float* bias; long ldc;   // bias: the expert's row at the tile's first column, or NULL
     int Mt, Nt, Kt;                  // valid extents of this tile / reduction length
 };
 
@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void ggemm_f32_kernel(GemmArgs g, int ntn)
         t.A = A + off * g.K + m0;      t.sam = 1;      t.sak = g.K;
         t.B = B + off * g.Nout + n0;   t.sbk = g.Nout; t.sbn = 1;
         t.C = (float*)g.C + ((size_t)e * g.K + m0) * g.Nout + n0;
-        t.C2 = nullptr; t.Z = nullptr; t.ldc = g.Nout;
+        t.C2 = nullptr; t.Z = nullptr; t.bias = nullptr; t.ldc = g.Nout;
         t.Mt = min(TM, g.K - m0); t.Nt = min(TN, g.Nout - n0); t.Kt = g.counts[e];
     } else {
         const int32_t* P = g.tileP + tile_height_index(TM) * (g.E + 1);
@@ -53,6 +53,7 @@ __global__ __launch_bounds__(256) void ggemm_f32_kernel(GemmArgs g, int ntn)
         t.C = (float*)g.C + r0 * g.Nout + n0;
         t.C2 = g.C2 ? (float*)g.C2 + r0 * g.Nout + n0 : nullptr;
         t.Z = g.Zin ? (const float*)g.Zin + r0 * g.Nout + n0 : nullptr;
+        t.bias = g.bias && (g.kind == kRowsNN || g.kind == kRowsNN_GeLU) ? (const float*)g.bias + (size_t)e * g.Nout + n0 : nullptr;
         t.ldc = g.Nout;
         t.Mt = min(TM, g.counts[e] - mt * TM); t.Nt = min(TN, g.Nout - n0); t.Kt = g.K;
     }
@@ -97,6 +98,7 @@ __global__ __launch_bounds__(256) void ggemm_f32_kernel(GemmArgs g, int ntn)
             if (n >= t.Nt) continue;
             const size_t o = (size_t)m * t.ldc + n;
             float v = acc[i][j];
+            if (t.bias) v += t.bias[n];
             switch (g.kind) {
                 case kRowsNN_GeLU: t.C[o] = v; t.C2[o] = gelu_f(v); break;
                 case kRowsNT_dGeLU: t.C[o] = v * gelu_grad_f(t.Z[o]); break;

@@ -242,7 +242,8 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     MOE_REQUIRE_PTR(X);
     MOE_REQUIRE_PTR(W1);
     MOE_REQUIRE_PTR(W2);
-    if (b1 || b2) { set_error("expert biases are not supported (b1 and b2 must be NULL)"); return MOE_ERR_UNSUPPORTED; }
+    if (b1 && !aligned16(b1)) { set_error("b1 is not 16-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    if (b2 && !aligned16(b2)) { set_error("b2 is not 16-byte aligned"); return MOE_ERR_INVALID_ARG; }
     WsLayout L;
     if ((s = check_ws(desc, workspace, workspace_bytes, &L)) != MOE_OK) return s;
     const moe_desc_t& D = *desc;
@@ -269,12 +270,12 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     a.clock_probe = (long long*)(ws + L.sk_error + 8);
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
-    a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h;
+    a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h; a.bias = b1;
     { ScopedTimer tm(S_FC1, st); run_gemm(D, a, st); }
     if ((s = check_launch("expert layer 1")) != MOE_OK) return s;
 
     a.kind = kRowsNN;       // Ys = H W2[e]
-    a.A = ws + L.H; a.B = W2; a.C = ws + L.Ys; a.C2 = nullptr; a.K = D.h; a.Nout = D.d;
+    a.A = ws + L.H; a.B = W2; a.C = ws + L.Ys; a.C2 = nullptr; a.K = D.h; a.Nout = D.d; a.bias = b2;
     { ScopedTimer tm(S_FC2, st); run_gemm(D, a, st); }
     if ((s = check_launch("expert layer 2")) != MOE_OK) return s;
 
@@ -359,6 +360,27 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
                         plan->perm, plan->counts, plan->offsets, dX, dWg, dbg, ws, st);
     }
     return check_launch("gate backward");
+}
+
+moe_status_t moe_bias_backward(const moe_desc_t* desc, const moe_plan_t* plan, float* db1, float* db2, void* workspace,
+                               size_t workspace_bytes, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    if (db1 && !aligned16(db1)) { set_error("db1 is not 16-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    if (db2 && !aligned16(db2)) { set_error("db2 is not 16-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    WsLayout L;
+    if ((s = check_ws(desc, workspace, workspace_bytes, &L)) != MOE_OK) return s;
+    const moe_desc_t& D = *desc;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    // z = xs W1 + b1 and ys = h W2 + b2 per row: the bias gradients are the column sums, over the expert's rows,
+    // of dZ and of dYs, which moe_backward left in the workspace.  (With N == 0 every sum is empty.)
+    if (db1) launch_segment_sums(D, L, ws + L.dZ, D.h, plan->counts, plan->offsets, db1, ws, st);
+    if (db2) launch_segment_sums(D, L, ws + L.dYs, D.d, plan->counts, plan->offsets, db2, ws, st);
+    return check_launch("expert bias gradients");
 }
 
 moe_status_t moe_scatter(const moe_desc_t* desc, const moe_plan_t* plan, const void* X, void* Xs, void* stream)

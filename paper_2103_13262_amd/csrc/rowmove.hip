@@ -196,7 +196,8 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
     const int e = lo;
     const int r0 = offsets[e] + (piece - P64[e]) * 64;
     const int r1 = min(r0 + 64, offsets[e] + counts[e]);
-    if (threadIdx.x < 64) s_g[threadIdx.x] = r0 + (int)threadIdx.x < r1 ? dl[perm[r0 + threadIdx.x]] : 0.f;
+    // (dl == nullptr: plain column sums of the segment, every row with weight 1: the expert-bias gradients)
+    if (threadIdx.x < 64) s_g[threadIdx.x] = r0 + (int)threadIdx.x < r1 ? (dl ? dl[perm[r0 + threadIdx.x]] : 1.f) : 0.f;
     __syncthreads();
     const int ct = threadIdx.x & 127, q = threadIdx.x >> 7;
     const int c = blockIdx.y * 128 + ct;
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
         float* dst = part + (size_t)piece * d + (size_t)c * V;
 #pragma unroll
         for (int u = 0; u < V; ++u) dst[u] = acc[u];
-        if (c == 0) {
+        if (c == 0 && bpart) {
             float sdl = 0.f;
             for (int i = 0; i < 64; ++i) sdl += s_g[i];
             bpart[piece] = sdl;
@@ -277,6 +278,18 @@ __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part,
         if (accumulate) s += dbg[e];
         dbg[e] = s;
     }
+}
+
+// out[e][c] = sum of the pieces of expert e, in ascending order (the column sums of its segment).
+__global__ __launch_bounds__(256) void segsum_final(const float* __restrict__ part, const int32_t* __restrict__ P64,
+                                                    float* __restrict__ out, int width, int accumulate)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x, e = blockIdx.y;
+    if (c >= width) return;
+    float s = 0.f;
+    for (int q = P64[e]; q < P64[e + 1]; ++q) s += part[(size_t)q * width + c];
+    const size_t o = (size_t)e * width + c;
+    out[o] = accumulate ? out[o] + s : s;
 }
 
 // ---- launchers -----------------------------------------------------------------------------------
@@ -355,6 +368,24 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
                            (long)D.N, D.k, cpr);
     }
+}
+
+// out[E][width] (float) = column sums of src[M][width] over every expert's segment (fixed order).
+void launch_segment_sums(const moe_desc_t& D, const WsLayout& L, const void* src, int width, const int32_t* counts,
+                         const int32_t* offsets, float* out, char* ws, hipStream_t st)
+{
+    const int cpr = (int)((size_t)width * dtype_size(D.dtype) / 16);
+    float* part = (float*)(ws + L.bias_part);
+    const int32_t* P64 = (const int32_t*)(ws + L.tileP) + tile_height_index(64) * (D.E + 1);
+    const dim3 pg((unsigned)L.dwg_pieces, (cpr + 127) / 128);
+    if (D.dtype == MOE_BF16)
+        hipLaunchKernelGGL(dwg_partial<unsigned short>, pg, dim3(512), 0, st, src, (const float*)nullptr,
+                           (const int32_t*)nullptr, counts, offsets, P64, part, (float*)nullptr, D.E, width, cpr);
+    else
+        hipLaunchKernelGGL(dwg_partial<float>, pg, dim3(512), 0, st, src, (const float*)nullptr, (const int32_t*)nullptr,
+                           counts, offsets, P64, part, (float*)nullptr, D.E, width, cpr);
+    hipLaunchKernelGGL(segsum_final, dim3((unsigned)((width + 255) / 256), (unsigned)D.E), dim3(256), 0, st,
+                       (const float*)part, P64, out, width, D.accumulate);
 }
 
 }  // namespace moe

@@ -24,6 +24,7 @@ class Workload:
     dtype: str      # "f32" | "bf16"  storage of X, weights, outputs
     zipf_s: float = 0.0   # 0: gate bias zero (near-uniform load); >0: expected load ~ (e+1)^-s
     seed: int = 0
+    bias_std: float = 0.0  # > 0: the experts have biases b1[E,h], b2[E,d] ~ N(0, bias_std) (the five workloads have none)
 
     @property
     def M(self):
@@ -76,7 +77,8 @@ def gate_bias(w: Workload):
 
 
 def make_inputs(w: Workload, with_dy=True):
-    """Returns dict of numpy arrays: X[N,d], Wg[d,E], bg[E] f32, W1[E,d,h], W2[E,h,d], dY[N,d].
+    """Returns dict of numpy arrays: X[N,d], Wg[d,E], bg[E] f32, W1[E,d,h], W2[E,h,d], dY[N,d]
+    (and b1[E,h], b2[E,d] when the workload has expert biases).
 
     For dtype "bf16" the tensors are uint16 bit patterns (exactly what both the
     oracle and the GPU receive); for "f32" they are float32.
@@ -89,6 +91,9 @@ def make_inputs(w: Workload, with_dy=True):
     }
     if with_dy:
         t["dY"] = _normal(w.seed, 5, (w.N, w.d), 1.0)
+    if w.bias_std > 0.0:
+        t["b1"] = _normal(w.seed, 6, (w.E, w.h), w.bias_std)
+        t["b2"] = _normal(w.seed, 7, (w.E, w.d), w.bias_std)
     if w.dtype == "bf16":
         t = {n: f32_to_bf16_bits(a) for n, a in t.items()}
     elif w.dtype != "f32":

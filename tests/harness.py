@@ -57,6 +57,10 @@ class GpuRun:
         self.X, self.Wg, self.W1, self.W2 = tt("X"), tt("Wg"), tt("W1"), tt("W2")
         self.dY = tt("dY") if "dY" in inputs else None
         self.bg = None if inputs.get("bg") is None else torch.from_numpy(inputs["bg"]).to(device)
+        self.b1 = tt("b1") if "b1" in inputs else None
+        self.b2 = tt("b2") if "b2" in inputs else None
+        self.db1 = torch.full((w.E, w.h), float("nan"), dtype=torch.float32, device=device)
+        self.db2 = torch.full((w.E, w.d), float("nan"), dtype=torch.float32, device=device)
         act = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         grd = torch.bfloat16 if gd == B.MOE_BF16 else torch.float32
         # outputs are poisoned so that an element the kernels skip shows up as a mismatch
@@ -73,13 +77,15 @@ class GpuRun:
 
     def forward(self):
         b = self.buf
-        B.moe_forward(self.desc, b.plan, self.X, self.W1, self.W2, None, None, self.Y, b.workspace, b.ws_bytes,
+        B.moe_forward(self.desc, b.plan, self.X, self.W1, self.W2, self.b1, self.b2, self.Y, b.workspace, b.ws_bytes,
                       b.stream())
 
     def backward(self):
         b = self.buf
         B.moe_backward(self.desc, b.plan, self.X, self.Wg, self.W1, self.W2, self.dY, self.dX, self.dWg, self.dbg,
                        self.dW1, self.dW2, b.workspace, b.ws_bytes, b.stream())
+        if self.b1 is not None or self.b2 is not None:
+            B.moe_bias_backward(self.desc, b.plan, self.db1, self.db2, b.workspace, b.ws_bytes, b.stream())
 
     def run(self, backward=True):
         self.plan()
@@ -118,8 +124,10 @@ def oracle_problem(w: Workload, inputs, dY=True):
     import oracle as orc
 
     bg = None if inputs.get("bg") is None else inputs["bg"].astype(np.float64)
+    wide = lambda a: None if a is None else (orc.bf16_bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64))
     return orc.OracleProblem(inputs["X"], inputs["Wg"], inputs["W1"], inputs["W2"], w.k, bg=bg,
-                             dY=inputs["dY"] if dY and "dY" in inputs else None)
+                             dY=inputs["dY"] if dY and "dY" in inputs else None, b1=wide(inputs.get("b1")),
+                             b2=wide(inputs.get("b2")))
 
 
 def check_plan_exact(run: GpuRun, inputs):

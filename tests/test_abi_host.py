@@ -100,6 +100,12 @@ def test_null_misaligned_and_small_workspace_arguments():
     with pytest.raises(B.MoeError) as ei:
         B.moe_scatter_backward(d, plan, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, ws - 1)
     assert ei.value.status == B.MOE_ERR_WORKSPACE
-    with pytest.raises(B.MoeError) as ei:                                                 # expert biases
-        B.moe_forward(d, plan, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, ws)
-    assert ei.value.status == B.MOE_ERR_UNSUPPORTED
+    for c in (lambda: B.moe_forward(d, plan, FAKE, FAKE, FAKE, FAKE + 2, None, FAKE, FAKE, ws),   # b1 misaligned
+              lambda: B.moe_bias_backward(d, plan, FAKE + 4, None, FAKE, ws),                          # db1 misaligned
+              lambda: B.moe_bias_backward(d, None, FAKE, FAKE, FAKE, ws)):                            # plan NULL
+        with pytest.raises(B.MoeError) as ei:
+            c()
+        assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_bias_backward(d, plan, FAKE, FAKE, FAKE, ws - 1)
+    assert ei.value.status == B.MOE_ERR_WORKSPACE

@@ -31,6 +31,11 @@ CASES = [
     Workload("wide_gate_slabs_bf16", 300, 288, 64, 100, 2, "bf16", 0.0, 24),
     Workload("wide_gate_slabs_f32", 150, 160, 64, 70, 3, "f32", 0.0, 25),
     Workload("gate_24_experts_f32", 130, 96, 64, 24, 2, "f32", 0.0, 26),
+    # experts with biases (b1, b2 ~ N(0, 0.1), about the size of the pre-activations); the second has empty experts
+    # and tiles cut along the reduction
+    Workload("biases_f32", 220, 96, 160, 5, 2, "f32", 0.0, 27, 0.1),
+    Workload("biases_bf16", 700, 128, 1024, 6, 2, "bf16", 0.7, 28, 0.1),
+    Workload("biases_sparse_bf16", 40, 64, 96, 48, 2, "bf16", 0.0, 29, 0.1),
     # few output tiles with a deep reduction: the tiles of the second and fourth grouped product are cut into
     # pieces of their reduction; in the first case a workgroup ends one tile and begins the next
     Workload("split_reduction_bf16", 360, 64, 384, 12, 2, "bf16", 0.0, 22),
@@ -70,6 +75,9 @@ def _full_check(w, grad_dtype=None, few_rows_per_expert=False):
     errs["dX"] = rel_err(to_numpy64(run.dX)[:w.N], ref["dX"])
     errs["dWg"] = rel_err(to_numpy64(run.dWg), ref["dWg"])
     errs["dbg"] = rel_err(to_numpy64(run.dbg)[:w.E], ref["dbg"])
+    if w.bias_std > 0.0:                # expert-bias gradients (fp32 sums of the stored dZ and dYs rows)
+        errs["db1"] = rel_err(to_numpy64(run.db1), ref["db1"])
+        errs["db2"] = rel_err(to_numpy64(run.db2), ref["db2"])
     # Weight gradients expert by expert, each against the RMS of the whole tensor.  With fewer than 64 rows an
     # element is a sum of few products of bf16-rounded operands (H, dYs, dZ are stored in bf16: 3 roundings of
     # 2^-8 each per term) with no averaging over rows; where the terms cancel, the worst of d*h elements
@@ -98,6 +106,8 @@ def _full_check(w, grad_dtype=None, few_rows_per_expert=False):
     # empty experts receive exact zeros
     for e in np.nonzero(ref_plan["counts"] == 0)[0]:
         assert not np.any(to_numpy64(run.dW1[e])) and not np.any(to_numpy64(run.dW2[e]))
+        if w.bias_std > 0.0:
+            assert not np.any(to_numpy64(run.db1[e])) and not np.any(to_numpy64(run.db2[e]))
     if w.k == 1:                        # softmax over one logit: no gradient reaches the gate
         assert not np.any(run.region("dl")) and not np.any(to_numpy64(run.dWg)) and not np.any(to_numpy64(run.dbg)[:w.E])
     return run, inputs, ref
