@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs,
 
 // ---- dWg[:,e] = sum over rows r of segment e of dl[perm[r]] * Xs[r,:]  (fixed order) ----------
 // Every expert's segment is cut into pieces of 64 rows (the 64-row tile table of the plan step), so the
-// work per workgroup is the same however skewed the load is.  grid (max pieces, ceil(cpr/128)); each thread
+// work per workgroup is the same however skewed the load is.  grid (max pieces, ceil(cpr/64)); each thread
 // owns one 16-byte column piece and walks the rows of its piece; a second kernel adds an expert's pieces
 // in ascending order.
 template <typename T>
@@ -181,11 +181,11 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
                                                    float* __restrict__ part, float* __restrict__ bpart, int E, int d,
                                                    int cpr)
 {
-    // 128 column threads x 4 row groups: group q walks rows 16q .. 16q+15 of the piece; the groups' sums are added
-    // in the order ((0 + 1) + 2) + 3, so the result does not depend on timing.
+    // 64 column threads x 8 row groups: group q walks rows 8q .. 8q+7 of the piece (all eight loads in flight); the
+    // groups' sums are added in the order (((0 + 1) + 2) + ...) + 7, so the result does not depend on timing.
     constexpr int V = Vec<T>::N;
     __shared__ float s_g[64];
-    __shared__ float s_acc[3][128][V];
+    __shared__ float s_acc[7][64][V];
     const int piece = blockIdx.x;
     if (piece >= P64[E]) return;          // uniform over the workgroup
     int lo = 0, hi = E;                   // largest e with P64[e] <= piece
@@ -199,29 +199,26 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
     // (dl == nullptr: plain column sums of the segment, every row with weight 1: the expert-bias gradients)
     if (threadIdx.x < 64) s_g[threadIdx.x] = r0 + (int)threadIdx.x < r1 ? (dl ? dl[perm[r0 + threadIdx.x]] : 1.f) : 0.f;
     __syncthreads();
-    const int ct = threadIdx.x & 127, q = threadIdx.x >> 7;
-    const int c = blockIdx.y * 128 + ct;
+    const int ct = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int c = blockIdx.y * 64 + ct;
     const bool active = c < cpr;
     float acc[V];
 #pragma unroll
     for (int u = 0; u < V; ++u) acc[u] = 0.f;
     if (active) {
+        float v[8][V];
 #pragma unroll
-        for (int i0 = 0; i0 < 16; i0 += 4) {
-            float v[4][V];
+        for (int i = 0; i < 8; ++i) {         // rows past the end of the piece contribute g = 0; their loads are skipped
+            const int r = r0 + q * 8 + i;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {     // rows past the end of the piece contribute g = 0; their loads are skipped
-                const int r = r0 + q * 16 + i0 + i;
+            for (int u = 0; u < V; ++u) v[i][u] = 0.f;
+            if (r < r1) Vec<T>::load(Xs, (size_t)r * cpr + c, v[i]);
+        }
 #pragma unroll
-                for (int u = 0; u < V; ++u) v[i][u] = 0.f;
-                if (r < r1) Vec<T>::load(Xs, (size_t)r * cpr + c, v[i]);
-            }
+        for (int i = 0; i < 8; ++i) {
+            const float g = s_g[q * 8 + i];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float g = s_g[q * 16 + i0 + i];
-#pragma unroll
-                for (int u = 0; u < V; ++u) acc[u] = fmaf(g, v[i][u], acc[u]);
-            }
+            for (int u = 0; u < V; ++u) acc[u] = fmaf(g, v[i][u], acc[u]);
         }
     }
     if (q > 0) {
@@ -231,7 +228,7 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
     __syncthreads();
     if (q == 0 && active) {
 #pragma unroll
-        for (int g = 0; g < 3; ++g)
+        for (int g = 0; g < 7; ++g)
 #pragma unroll
             for (int u = 0; u < V; ++u) acc[u] += s_acc[g][ct][u];
         float* dst = part + (size_t)piece * d + (size_t)c * V;
@@ -342,7 +339,7 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     float* part = (float*)(ws + L.dwg_part);
     float* bpart = (float*)(ws + L.dbg_part);
     const int32_t* P64 = (const int32_t*)(ws + L.tileP) + tile_height_index(64) * (D.E + 1);
-    const dim3 pg((unsigned)L.dwg_pieces, (cpr + 127) / 128);
+    const dim3 pg((unsigned)L.dwg_pieces, (cpr + 63) / 64);
     const dim3 fg((unsigned)((D.d + 255) / 256), (unsigned)D.E);
     const unsigned xg = grid_for((long)D.N * cpr);
     const unsigned tg = (unsigned)(((long)D.d * D.E + 255) / 256);
@@ -377,7 +374,7 @@ void launch_segment_sums(const moe_desc_t& D, const WsLayout& L, const void* src
     const int cpr = (int)((size_t)width * dtype_size(D.dtype) / 16);
     float* part = (float*)(ws + L.bias_part);
     const int32_t* P64 = (const int32_t*)(ws + L.tileP) + tile_height_index(64) * (D.E + 1);
-    const dim3 pg((unsigned)L.dwg_pieces, (cpr + 127) / 128);
+    const dim3 pg((unsigned)L.dwg_pieces, (cpr + 63) / 64);
     if (D.dtype == MOE_BF16)
         hipLaunchKernelGGL(dwg_partial<unsigned short>, pg, dim3(512), 0, st, src, (const float*)nullptr,
                            (const int32_t*)nullptr, counts, offsets, P64, part, (float*)nullptr, D.E, width, cpr);
