@@ -125,17 +125,6 @@ __global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY
     }
 }
 
-// ---- WgT[e][i] = Wg[i][e]: lets the kernel below read a gate column as contiguous 16-byte pieces ----
-template <typename T>
-__global__ __launch_bounds__(256) void transpose_gate(const T* __restrict__ Wg, T* __restrict__ WgT, int d, int E)
-{
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;   // index into WgT
-    if (i < (long)d * E) {
-        const int e = (int)(i / d), row = (int)(i % d);
-        WgT[i] = Wg[(size_t)row * E + e];
-    }
-}
-
 // ---- dX[t,:] = sum_j dXs[pos[a],:] + sum_j dl[a] * Wg[:, idx[a]] ------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs, const void* __restrict__ WgT,
@@ -179,8 +168,17 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
                                                    const int32_t* __restrict__ perm, const int32_t* __restrict__ counts,
                                                    const int32_t* __restrict__ offsets, const int32_t* __restrict__ P64,
                                                    float* __restrict__ part, float* __restrict__ bpart, int E, int d,
-                                                   int cpr)
+                                                   int cpr, const T* __restrict__ Wg, T* __restrict__ WgT)
 {
+    // Rides along (WgT != nullptr): WgT[e][i] = Wg[i][e], which lets the kernel that follows the reduction read a
+    // gate column as contiguous 16-byte pieces; spread over all workgroups of the launch.
+    if (WgT) {
+        const long nel = (long)d * E, nthr = (long)gridDim.x * gridDim.y * 512;
+        for (long i = ((long)blockIdx.y * gridDim.x + blockIdx.x) * 512 + threadIdx.x; i < nel; i += nthr) {
+            const int ee = (int)(i / d), row = (int)(i - (long)ee * d);
+            WgT[i] = Wg[(size_t)row * E + ee];
+        }
+    }
     // 64 column threads x 8 row groups: group q walks rows 8q .. 8q+7 of the piece (all eight loads in flight); the
     // groups' sums are added in the order (((0 + 1) + 2) + ...) + 7, so the result does not depend on timing.
     constexpr int V = Vec<T>::N;
@@ -342,12 +340,11 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     const dim3 pg((unsigned)L.dwg_pieces, (cpr + 63) / 64);
     const dim3 fg((unsigned)((D.d + 255) / 256), (unsigned)D.E);
     const unsigned xg = grid_for((long)D.N * cpr);
-    const unsigned tg = (unsigned)(((long)D.d * D.E + 255) / 256);
     void* WgT = ws + L.WgT;
     if (D.dtype == MOE_BF16) {
         using T = unsigned short;
-        hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
-        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
+        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr,
+                           (const T*)Wg, (T*)WgT);
         if (D.grad_dtype == MOE_BF16)
             hipLaunchKernelGGL(dwg_final<unsigned short>, fg, dim3(256), 0, st, (const float*)part,
                                (const float*)bpart, P64, (unsigned short*)dWg, dbg, D.d, D.E, D.accumulate);
@@ -358,8 +355,8 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
                            (long)D.N, D.k, cpr);
     } else {
         using T = float;
-        hipLaunchKernelGGL(transpose_gate<T>, dim3(tg), dim3(256), 0, st, (const T*)Wg, (T*)WgT, D.d, D.E);
-        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr);
+        hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr,
+                           (const T*)Wg, (T*)WgT);
         hipLaunchKernelGGL(dwg_final<float>, fg, dim3(256), 0, st, (const float*)part, (const float*)bpart,
                            P64, (float*)dWg, dbg, D.d, D.E, D.accumulate);
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
@@ -377,10 +374,11 @@ void launch_segment_sums(const moe_desc_t& D, const WsLayout& L, const void* src
     const dim3 pg((unsigned)L.dwg_pieces, (cpr + 63) / 64);
     if (D.dtype == MOE_BF16)
         hipLaunchKernelGGL(dwg_partial<unsigned short>, pg, dim3(512), 0, st, src, (const float*)nullptr,
-                           (const int32_t*)nullptr, counts, offsets, P64, part, (float*)nullptr, D.E, width, cpr);
+                           (const int32_t*)nullptr, counts, offsets, P64, part, (float*)nullptr, D.E, width, cpr,
+                           (const unsigned short*)nullptr, (unsigned short*)nullptr);
     else
         hipLaunchKernelGGL(dwg_partial<float>, pg, dim3(512), 0, st, src, (const float*)nullptr, (const int32_t*)nullptr,
-                           counts, offsets, P64, part, (float*)nullptr, D.E, width, cpr);
+                           counts, offsets, P64, part, (float*)nullptr, D.E, width, cpr, (const float*)nullptr, (float*)nullptr);
     hipLaunchKernelGGL(segsum_final, dim3((unsigned)((width + 255) / 256), (unsigned)D.E), dim3(256), 0, st,
                        (const float*)part, P64, out, width, D.accumulate);
 }
