@@ -36,6 +36,10 @@ CASES = [
     Workload("biases_f32", 220, 96, 160, 5, 2, "f32", 0.0, 27, 0.1),
     Workload("biases_bf16", 700, 128, 1024, 6, 2, "bf16", 0.7, 28, 0.1),
     Workload("biases_sparse_bf16", 40, 64, 96, 48, 2, "bf16", 0.0, 29, 0.1),
+    # the limits of the description: 1024 experts with top-8, and a batch of many plan chunks
+    Workload("max_experts_top8_bf16", 300, 64, 32, 1024, 8, "bf16", 0.0, 30),
+    Workload("many_tokens_f32", 70000, 32, 32, 6, 2, "f32", 0.6, 31),
+    Workload("many_tokens_bf16", 90000, 32, 64, 40, 1, "bf16", 1.0, 32),
     # few output tiles with a deep reduction: the tiles of the second and fourth grouped product are cut into
     # pieces of their reduction; in the first case a workgroup ends one tile and begins the next
     Workload("split_reduction_bf16", 360, 64, 384, 12, 2, "bf16", 0.0, 22),
