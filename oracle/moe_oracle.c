@@ -17,7 +17,8 @@
  *   - G(x) is one fully-connected layer: l = x W_g + b_g (Section 5.2).
  *   - ArgMax_k ranks the raw logits; equal logits go to the lower expert id;
  *     slot j holds the j-th largest.
- *   - score_i is the softmax over the k selected logits (weights sum to 1).
+ *   - score_i is the softmax over the k selected logits (weights sum to 1); with score_all = 1 it is
+ *     the softmax over all E logits taken at the selected experts (Algorithm 1 read literally).
  *   - the expert is W2^T GeLU(W1^T x + b1) + b2 with the exact erf GeLU; the
  *     biases are optional (the paper's expert is "an FFN": two linear layers).
  *   - inside an expert's contiguous segment rows keep assignment order
@@ -55,6 +56,10 @@ typedef struct {
     const void *dY;       /* [N, d] or NULL (forward only)                        */
     const double *b1;     /* [E, h] expert biases of the first layer, or NULL     */
     const double *b2;     /* [E, d] expert biases of the second layer, or NULL    */
+    int32_t score_all;    /* 0: score = softmax over the k selected logits;
+                             1: score = softmax over all E logits, taken at the selected experts
+                                (Algorithm 1 read literally with G = softmax of the linear layer:
+                                the scores of a token then sum to less than 1)           */
 } orc_problem;
 
 static inline double ld(const void *p, int dtype, size_t i)
@@ -101,6 +106,10 @@ static void gate_token(const orc_problem *p, int t, double *logit /*[E]*/, int32
     for (int j = 0; j < k; ++j) {
         w[j] = exp(logit[idx[j]] - logit[idx[0]]);
         den += w[j];
+    }
+    if (p->score_all) {        /* the normaliser runs over every expert (idx[0] holds the largest logit) */
+        den = 0.0;
+        for (int e = 0; e < E; ++e) den += exp(logit[e] - logit[idx[0]]);
     }
     for (int j = 0; j < k; ++j) w[j] /= den;
 }
@@ -269,8 +278,28 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
                 dw[j] = acc;
                 s += w[j] * acc;
             }
+            /* (the same expression serves both score modes: with score_all the w_j are the softmax probabilities
+             * p_e of the selected experts, d p_a / d l_b = p_a (delta_ab - p_b), so for a selected expert
+             * dL/dl = w_j dw_j - w_j sum_i w_i dw_i; the experts that were not selected follow below) */
             for (int j = 0; j < k; ++j) dl[j] = w[j] * (dw[j] - s);
             if (dl_out) memcpy(dl_out + (size_t)n * k, dl, sizeof(double) * (size_t)k);
+            if (p->score_all) {
+                /* an expert b that was not selected: dL/dl_b = sum_j dw_j p_j (0 - p_b) = -p_b s */
+                const double top = logit[idx[0]];
+                double den = 0.0;
+                for (int e = 0; e < E; ++e) den += exp(logit[e] - top);
+                for (int e = 0; e < E; ++e) {
+                    int sel = 0;
+                    for (int j = 0; j < k; ++j) sel |= (idx[j] == e);
+                    if (sel) continue;
+                    const double dle = -(exp(logit[e] - top) / den) * s;
+                    if (dbg) dbg[e] += dle;
+                    for (int i = 0; i < d; ++i) {
+                        if (dWg) dWg[(size_t)i * E + e] += dle * x[i];
+                        dx[i] += dle * ld(p->Wg, dt, (size_t)i * E + e);
+                    }
+                }
+            }
             /* l = x Wg + bg */
             for (int j = 0; j < k; ++j) {
                 const int e = idx[j];

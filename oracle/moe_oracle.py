@@ -21,7 +21,7 @@ class _Problem(C.Structure):
         ("dtype", C.c_int32),
         ("X", C.c_void_p), ("Wg", C.c_void_p), ("bg", C.c_void_p),
         ("W1", C.c_void_p), ("W2", C.c_void_p), ("dY", C.c_void_p),
-        ("b1", C.c_void_p), ("b2", C.c_void_p),
+        ("b1", C.c_void_p), ("b2", C.c_void_p), ("score_all", C.c_int32),
     ]
 
 
@@ -61,7 +61,7 @@ def bf16_bits_to_f64(a):
 class OracleProblem:
     """X[N,d], Wg[d,E], W1[E,d,h], W2[E,h,d], optional bg[E], b1[E,h], b2[E,d] (float64), optional dY[N,d]."""
 
-    def __init__(self, X, Wg, W1, W2, k, bg=None, dY=None, b1=None, b2=None):
+    def __init__(self, X, Wg, W1, W2, k, bg=None, dY=None, b1=None, b2=None, score_all=False):
         arrs = [np.ascontiguousarray(a) for a in (X, Wg, W1, W2)]
         self.X, self.Wg, self.W1, self.W2 = arrs
         self.dY = None if dY is None else np.ascontiguousarray(dY)
@@ -82,7 +82,9 @@ class OracleProblem:
         assert self.b2 is None or self.b2.shape == (self.E, self.d)
         self.k = int(k)
         self._c = _Problem(self.N, self.d, self.h, self.E, self.k, code, _ptr(self.X), _ptr(self.Wg),
-                           _ptr(self.bg), _ptr(self.W1), _ptr(self.W2), _ptr(self.dY), _ptr(self.b1), _ptr(self.b2))
+                           _ptr(self.bg), _ptr(self.W1), _ptr(self.W2), _ptr(self.dY), _ptr(self.b1), _ptr(self.b2),
+                           1 if score_all else 0)
+        self.score_all = bool(score_all)
 
 
 def num_threads():

@@ -286,6 +286,66 @@ def test_gradients_match_central_differences(k, E):
             assert np.abs(grad).max() > 1e-3          # the gate really receives gradient via the score
 
 
+# ------------------------------------------------------------------ scores = softmax over all experts
+def _all(p, **kw):
+    return orc.OracleProblem(p.X, p.Wg, p.W1, p.W2, p.k, bg=p.bg, dY=p.dY, b1=p.b1, b2=p.b2, score_all=True, **kw)
+
+
+def test_scores_over_all_experts_are_the_softmax_probabilities_of_the_selected():
+    p = _rand_problem(61, N=9, d=4, h=5, E=6, k=2)
+    base, out = orc.layer(p), orc.layer(_all(p))
+    prob = softmax(p.X @ p.Wg + p.bg, axis=1)
+    np.testing.assert_array_equal(out["idx"], base["idx"])                     # the selection does not change
+    np.testing.assert_allclose(out["w"], np.take_along_axis(prob, out["idx"], 1), rtol=1e-13)
+    assert np.all(out["w"].sum(1) < 1.0)
+    # the two score modes differ by one factor per token: the probability mass of the selected experts
+    mass = out["w"].sum(1, keepdims=True)
+    np.testing.assert_allclose(out["w"], base["w"] * mass, rtol=1e-12)
+    np.testing.assert_allclose(out["Y"], base["Y"] * mass, rtol=1e-11, atol=1e-13)
+
+
+def test_scores_over_all_experts_equal_the_other_mode_when_every_expert_is_selected():
+    p = _rand_problem(62, N=6, d=4, h=5, E=3, k=3)
+    a, b = orc.layer(p), orc.layer(_all(p))
+    for n in ("Y", "dX", "dW1", "dW2", "dWg", "dbg", "w", "dl"):
+        np.testing.assert_allclose(b[n], a[n], rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("k,E", [(2, 5), (1, 4)])
+def test_scores_over_all_experts_gradients_match_central_differences(k, E):
+    for seed in range(70, 90):
+        p = _rand_problem(seed, N=4, d=3, h=5, E=E, k=k)
+        _, _, logits = orc.gate(p)
+        srt = -np.sort(-logits, axis=1)
+        if np.min(srt[:, :k] - srt[:, 1:k + 1]) > 5e-2:
+            break
+    else:
+        pytest.skip("no seed with a safe decision gap")
+    p = _all(p)
+    out = orc.layer(p)
+    loss = lambda: float((orc.layer(orc.OracleProblem(p.X, p.Wg, p.W1, p.W2, p.k, bg=p.bg, score_all=True))["Y"] * p.dY).sum())
+    eps = 1e-6
+    for name, grad in (("X", out["dX"]), ("Wg", out["dWg"]), ("bg", out["dbg"]), ("W1", out["dW1"]), ("W2", out["dW2"])):
+        arr = getattr(p, name)
+        num = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            old = arr[i]
+            arr[i] = old + eps
+            lp = loss()
+            arr[i] = old - eps
+            lm = loss()
+            arr[i] = old
+            num[i] = (lp - lm) / (2 * eps)
+        scale = max(1.0, np.abs(num).max())
+        assert np.max(np.abs(num - grad)) / scale < 2e-8, name
+    # in this mode the gate is trained through the score even with one expert per token, and every expert's
+    # column of the gate matrix receives gradient, selected or not
+    assert np.abs(out["dWg"]).min(axis=0).max() > 0 and np.all(np.abs(out["dWg"]).max(axis=0) > 1e-6)
+    assert np.abs(out["dbg"]).sum() > 1e-3 and abs(out["dbg"].sum()) < 1e-12 * max(1.0, np.abs(out["dbg"]).sum()) * 1e3
+
+
 def test_k1_passes_no_gradient_to_the_gate():
     out = orc.layer(_rand_problem(9, k=1))
     assert np.all(out["dl"] == 0) and np.all(out["dWg"] == 0) and np.all(out["dbg"] == 0)
