@@ -67,7 +67,12 @@ typedef struct {
     int32_t grad_dtype; /* moe_dtype_t of dW1, dW2, dW_g: equal to dtype, or MOE_F32          */
     int32_t accumulate; /* 0: weight gradients are overwritten (zeros for an expert that got
                            no row); 1: added to what the buffers hold                         */
-    int32_t reserved[8]; /* must be zero                                                      */
+    int32_t score_all;  /* 0: the scores of a token are the softmax over its k selected logits
+                           (they sum to 1); 1: the softmax over all E logits, taken at the
+                           selected experts (Algorithm 1 read literally with a softmax gate:
+                           they sum to less than 1, and every expert's gate column, selected or
+                           not, receives gradient - also with k = 1)                           */
+    int32_t reserved[7]; /* must be zero                                                      */
 } moe_desc_t;
 
 /* Routing of one batch; six caller-owned device arrays that moe_plan fills and

@@ -20,7 +20,7 @@ EXPORTS = ("moe_workspace_bytes", "moe_workspace_region", "moe_plan", "moe_forwa
 class MoeDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("d", C.c_int32), ("h", C.c_int32), ("E", C.c_int32), ("k", C.c_int32),
                 ("dtype", C.c_int32), ("grad_dtype", C.c_int32), ("accumulate", C.c_int32),
-                ("reserved", C.c_int32 * 8)]
+                ("score_all", C.c_int32), ("reserved", C.c_int32 * 7)]
 
 
 class MoePlan(C.Structure):
@@ -95,8 +95,8 @@ def _check(status):
         raise MoeError(status, lib().moe_last_error().decode())
 
 
-def make_desc(N, d, h, E, k, dtype=MOE_BF16, grad_dtype=None, accumulate=0):
-    return MoeDesc(N, d, h, E, k, dtype, dtype if grad_dtype is None else grad_dtype, accumulate)
+def make_desc(N, d, h, E, k, dtype=MOE_BF16, grad_dtype=None, accumulate=0, score_all=0):
+    return MoeDesc(N, d, h, E, k, dtype, dtype if grad_dtype is None else grad_dtype, accumulate, score_all)
 
 
 def moe_workspace_bytes(desc):

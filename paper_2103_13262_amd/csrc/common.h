@@ -27,6 +27,15 @@ struct WsLayout {
     size_t dwg_part;  // [pieces][d] float: partial sums of dWg over pieces of 64 rows
     size_t dbg_part;  // [pieces] float
     size_t bias_part; // [pieces][max(d,h)] float: partial column sums for the expert-bias gradients
+    // only with desc.score_all (scores = softmax over all experts):
+    size_t logits;    // [N][E] double: the gate logits
+    size_t lse;       // [N] double: log of the sum of exp of a token's logits
+    size_t gate_S;    // [N] float: sum_j w_j dL/dw_j of a token
+    size_t gate_R;    // [N][E] float: dL/dlogit of the experts that were not selected (0 at the selected ones)
+    size_t dx_dense;  // [N][d] float: their contribution to dX
+    size_t dense_part;   // [ceil(N/512)][E][d] float: their contribution to dWg, by chunk of 512 tokens
+    size_t dense_bpart;  // [ceil(N/512)][E] float: and to dbg
+    int dense_chunks;
     size_t WgT;       // [E][d] gate matrix transposed (written by the plan step for E > 32 and by the backward pass), element type = desc.dtype
     size_t zeros;     // 1 KB of zeros (written by the plan step): source of masked reduction rows
     size_t sk_flags;  // [kMaxPersistentWgs] int32, directly behind the zero page and zeroed with it: "partial sum ready"
@@ -64,6 +73,16 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.dbg_part = take((size_t)L.dwg_pieces * sizeof(float));
     L.bias_part = take((size_t)L.dwg_pieces * (D.d > D.h ? D.d : D.h) * sizeof(float));
     L.WgT = take((size_t)D.E * D.d * b);
+    L.dense_chunks = (D.N + 511) / 512;
+    if (D.score_all) {
+        L.logits = take((size_t)D.N * D.E * sizeof(double));
+        L.lse = take((size_t)D.N * sizeof(double));
+        L.gate_S = take((size_t)D.N * sizeof(float));
+        L.gate_R = take((size_t)D.N * D.E * sizeof(float));
+        L.dx_dense = take((size_t)D.N * D.d * sizeof(float));
+        L.dense_part = take((size_t)L.dense_chunks * D.E * D.d * sizeof(float));
+        L.dense_bpart = take((size_t)L.dense_chunks * D.E * sizeof(float));
+    }
     L.zeros = take(kZeroedBytes);
     L.sk_flags = L.zeros + 1024;
     L.sk_error = L.sk_flags + kMaxPersistentWgs * sizeof(int32_t);
@@ -78,7 +97,8 @@ moe_status_t check_launch(const char* what);
 
 // ---- kernel launchers (each enqueues on `st`; operand shapes are validated by the callers) ----
 void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
-                      float* topk_w, void* WgT, hipStream_t st);   // WgT: [E][d] scratch for the transposed gate matrix
+                      float* topk_w, void* WgT, double* logits, double* lse, hipStream_t st);
+// (WgT: [E][d] scratch for the transposed gate matrix; logits [N][E] and lse [N]: only with desc.score_all, else NULL)
 void launch_plan(const moe_desc_t& D, const WsLayout& L, const int32_t* topk_idx, int32_t* counts,
                  int32_t* offsets, int32_t* pos, int32_t* perm, char* ws, hipStream_t st);
 
@@ -86,11 +106,13 @@ void launch_scatter(const moe_desc_t& D, const void* X, const int32_t* perm, voi
 void launch_combine(const moe_desc_t& D, const void* Ys, const float* topk_w, const int32_t* pos, void* Y,
                     hipStream_t st);
 void launch_dcombine(const moe_desc_t& D, const void* dY, const void* Ys, const float* topk_w,
-                     const int32_t* pos, void* dYs, float* dl, hipStream_t st);
+                     const int32_t* pos, void* dYs, float* dl, float* S_out, hipStream_t st);
 void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, const void* dXs, const void* Wg,
                      const float* dl, const int32_t* topk_idx, const int32_t* pos, const int32_t* perm,
                      const int32_t* counts, const int32_t* offsets, void* dX, void* dWg, float* dbg, char* ws,
-                     hipStream_t st);
+                     const void* X_dense, hipStream_t st);
+void launch_gate_dense(const moe_desc_t& D, const WsLayout& L, const void* X, const void* Wg, const int32_t* topk_idx,
+                       char* ws, hipStream_t st);
 
 // Grouped matrix products over the expert segments.
 //   kRows*: C[r,:] (r in segment e) = A[r,:] * op(B[e]);  A is [M,K] row-major, C is [M,Nout] row-major.

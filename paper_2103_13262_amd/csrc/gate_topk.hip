@@ -72,7 +72,8 @@ typedef __attribute__((ext_vector_type(4))) double f64x4;
 template <typename T>
 __global__ __launch_bounds__(256) void gate_mfma16_kernel(const T* __restrict__ X, const T* __restrict__ Wg,
                                                           const float* __restrict__ bg, int N, int d, int E, int k,
-                                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w)
+                                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                          double* __restrict__ logits_out)
 {
     constexpr int V = 16 / sizeof(T);                // elements per 16-byte piece
     constexpr int DC = 256;                          // features per slab
@@ -161,6 +162,7 @@ __global__ __launch_bounds__(256) void gate_mfma16_kernel(const T* __restrict__ 
         if (bg && e < E) l += (double)bg[e];
         if (!(l == l) || e >= E) l = -__builtin_inf();   // NaN ranks last; columns past E never win
         sL[i] = l;
+        if (logits_out && e < E && tok0 + (i >> 4) < N) logits_out[(size_t)(tok0 + (i >> 4)) * E + e] = l;
     }
     __syncthreads();
     {
@@ -192,10 +194,10 @@ __global__ __launch_bounds__(256) void gate_mfma16_kernel(const T* __restrict__ 
 
 template <typename T>
 static void launch_mfma16(const moe_desc_t& D, const T* X, const T* Wg, const float* bg, int32_t* idx, float* w,
-                          hipStream_t st)
+                          double* logits, hipStream_t st)
 {
     hipLaunchKernelGGL(gate_mfma16_kernel<T>, dim3((unsigned)((D.N + 15) / 16)), dim3(256), 0, st, X, Wg, bg, D.N, D.d, D.E,
-                       D.k, idx, w);
+                       D.k, idx, w, logits);
 }
 
 // ---- 17 to 32 experts -----------------------------------------------------------------------------------------
@@ -207,7 +209,8 @@ static void launch_mfma16(const moe_desc_t& D, const T* X, const T* Wg, const fl
 template <typename T, int NT>
 __global__ __launch_bounds__(256) void gate_mfma_kernel(const T* __restrict__ X, const T* __restrict__ Wg,
                                                         const float* __restrict__ bg, int N, int d, int E, int k,
-                                                        int32_t* __restrict__ topk_idx, float* __restrict__ topk_w)
+                                                        int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                        double* __restrict__ logits_out)
 {
     constexpr int KC = 32, V = 16 / sizeof(T), NPX = 8 / V;   // features per slab; 16-byte pieces per thread
     constexpr int EB = 16 * NT;                               // experts per block (NT groups of 16)
@@ -279,6 +282,7 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const T* __restrict__ X,
             if (ge < E) {                                    // wave-uniform
                 double l = sL[lane * 64 + wave * (EB / 4) + e] + (bg ? (double)bg[ge] : 0.0);
                 if (!(l == l)) l = ninf;                     // NaN ranks last; indices stay in range
+                if (logits_out && tok0 + lane < N) logits_out[(size_t)(tok0 + lane) * E + ge] = l;
                 topk_insert(l, ge, v, id, k);
             }
         }
@@ -339,7 +343,8 @@ __global__ __launch_bounds__(256) void gate_transpose(const T* __restrict__ Wg, 
 template <typename T, int MT>
 __global__ __launch_bounds__(256) void gate_mfma_wide_kernel(const T* __restrict__ X, const T* __restrict__ WgT,
                                                              const float* __restrict__ bg, int N, int d, int E, int k,
-                                                             int32_t* __restrict__ topk_idx, float* __restrict__ topk_w)
+                                                             int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                             double* __restrict__ logits_out)
 {
     constexpr int V = 16 / sizeof(T);                // elements per 16-byte piece
     constexpr int DC = 512 / sizeof(T);              // features per slab
@@ -444,6 +449,7 @@ __global__ __launch_bounds__(256) void gate_mfma_wide_kernel(const T* __restrict
             if (ge < E) {                            // wave-uniform
                 double l = sL[(lane % TT) * 64 + wave * 16 + e] + (bg ? (double)bg[ge] : 0.0);
                 if (!(l == l)) l = ninf;             // NaN ranks last; indices stay in range
+                if (logits_out && lane < TT && tok0 + lane < N) logits_out[(size_t)(tok0 + lane) * E + ge] = l;
                 topk_insert(l, ge, v, id, k);
             }
         }
@@ -485,7 +491,7 @@ __global__ __launch_bounds__(256) void gate_mfma_wide_kernel(const T* __restrict
 
 template <typename T, int MT>
 static void launch_wide_mt(const moe_desc_t& D, const T* X, const T* WgT, const float* bg, int32_t* idx, float* w,
-                           hipStream_t st)
+                           double* logits, hipStream_t st)
 {
     constexpr int S = 512 / (int)sizeof(T) + 16 / (int)sizeof(T);
     constexpr int slab = (16 * MT + 64) * S * (int)sizeof(T), merge = 4 * kMaxK * 64 * (8 + 4);
@@ -497,39 +503,61 @@ static void launch_wide_mt(const moe_desc_t& D, const T* X, const T* WgT, const 
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)((D.N + 16 * MT - 1) / (16 * MT))), dim3(256), smem, st, X, WgT, bg, D.N, D.d,
-                       D.E, D.k, idx, w);
+                       D.E, D.k, idx, w, logits);
 }
 
 template <typename T>
 static void launch_mfma(const moe_desc_t& D, const T* X, const T* Wg, const float* bg, int32_t* idx, float* w, T* WgT,
-                        hipStream_t st)
+                        double* logits, hipStream_t st)
 {
     if (D.E <= 32) {
         hipLaunchKernelGGL((gate_mfma_kernel<T, 2>), dim3((unsigned)((D.N + 63) / 64)), dim3(256), 0, st, X, Wg, bg, D.N, D.d,
-                           D.E, D.k, idx, w);
+                           D.E, D.k, idx, w, logits);
         return;
     }
     const long n = (long)D.d * D.E;
     hipLaunchKernelGGL(gate_transpose<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, Wg, WgT, D.d, D.E);
     // as many tokens per workgroup as still leave two workgroups for every compute unit (one wavefront per SIMD
     // and workgroup: the second workgroup fills the matrix cores while the first stages a slab or waits)
-    if (D.N >= 64 * 512) launch_wide_mt<T, 4>(D, X, WgT, bg, idx, w, st);
-    else if (D.N >= 32 * 512) launch_wide_mt<T, 2>(D, X, WgT, bg, idx, w, st);
-    else launch_wide_mt<T, 1>(D, X, WgT, bg, idx, w, st);
+    if (D.N >= 64 * 512) launch_wide_mt<T, 4>(D, X, WgT, bg, idx, w, logits, st);
+    else if (D.N >= 32 * 512) launch_wide_mt<T, 2>(D, X, WgT, bg, idx, w, logits, st);
+    else launch_wide_mt<T, 1>(D, X, WgT, bg, idx, w, logits, st);
+}
+
+// Scores = softmax over all E logits, taken at the selected experts: one wavefront per token sums exp(l - top)
+// over the stored logits (lanes stride the experts, then a fixed butterfly), rewrites the k scores and keeps
+// log-sum-exp for the backward pass.
+__global__ __launch_bounds__(256) void gate_scores_all(const double* __restrict__ logits, const int32_t* __restrict__ topk_idx,
+                                                       int N, int E, int k, float* __restrict__ topk_w,
+                                                       double* __restrict__ lse)
+{
+    const int lane = threadIdx.x & 63;
+    const long t = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= N) return;
+    const double* l = logits + (size_t)t * E;
+    const double top = l[topk_idx[t * k]];           // slot 0 holds the largest logit
+    double s = 0.0;
+    for (int e = lane; e < E; e += 64) s += exp(l[e] - top);
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane < k) topk_w[t * k + lane] = (float)(exp(l[topk_idx[t * k + lane]] - top) / s);
+    if (lane == 0) lse[t] = top + log(s);
 }
 
 void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
-                      float* topk_w, void* WgT, hipStream_t st)
+                      float* topk_w, void* WgT, double* logits, double* lse, hipStream_t st)
 {
     if (D.dtype == MOE_BF16) {
         using T = unsigned short;
-        if (D.E <= 16) launch_mfma16<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, st);
-        else launch_mfma<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, (T*)WgT, st);
+        if (D.E <= 16) launch_mfma16<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, logits, st);
+        else launch_mfma<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, (T*)WgT, logits, st);
     } else {
         using T = float;
-        if (D.E <= 16) launch_mfma16<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, st);
-        else launch_mfma<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, (T*)WgT, st);
+        if (D.E <= 16) launch_mfma16<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, logits, st);
+        else launch_mfma<T>(D, (const T*)X, (const T*)Wg, bg, topk_idx, topk_w, (T*)WgT, logits, st);
     }
+    if (logits)
+        hipLaunchKernelGGL(gate_scores_all, dim3((unsigned)((D.N + 3) / 4)), dim3(256), 0, st, (const double*)logits,
+                           (const int32_t*)topk_idx, D.N, D.E, D.k, topk_w, lse);
 }
 
 }  // namespace moe

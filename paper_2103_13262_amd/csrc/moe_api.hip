@@ -88,7 +88,8 @@ static moe_status_t check_desc(const moe_desc_t* D)
     if (D->d % 32 || D->h % 32) { set_error("d=%d and h=%d must be multiples of 32", D->d, D->h); return MOE_ERR_UNSUPPORTED; }
     if (D->E > kMaxE) { set_error("E=%d exceeds %d", D->E, kMaxE); return MOE_ERR_UNSUPPORTED; }
     if (D->k > kMaxK) { set_error("k=%d exceeds %d", D->k, kMaxK); return MOE_ERR_UNSUPPORTED; }
-    for (int i = 0; i < 8; ++i)
+    if (D->score_all != 0 && D->score_all != 1) { set_error("score_all must be 0 or 1"); return MOE_ERR_INVALID_ARG; }
+    for (int i = 0; i < 7; ++i)
         if (D->reserved[i]) { set_error("reserved[%d] must be 0", i); return MOE_ERR_UNSUPPORTED; }
     const long long M = (long long)D->N * D->k;
     if (M > 0x7fffffffLL || M * (long long)(D->d > D->h ? D->d : D->h) > (1LL << 46)) {
@@ -220,7 +221,9 @@ moe_status_t moe_plan(const moe_desc_t* desc, const void* X, const void* Wg, con
     const moe_desc_t& D = *desc;
     if (D.N > 0) {
         ScopedTimer tm(S_GATE, st);
-        launch_gate_topk(D, X, Wg, bg, plan->topk_idx, plan->topk_w, (char*)workspace + L.WgT, st);
+        launch_gate_topk(D, X, Wg, bg, plan->topk_idx, plan->topk_w, (char*)workspace + L.WgT,
+                         D.score_all ? (double*)((char*)workspace + L.logits) : nullptr,
+                         D.score_all ? (double*)((char*)workspace + L.lse) : nullptr, st);
         if ((s = check_launch("gate/top-k")) != MOE_OK) return s;
     }
     // With N == 0 the plan kernels still run: they write counts = 0, offsets = 0 and empty tile tables.
@@ -311,7 +314,8 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
 
     if (D.N > 0) {
         ScopedTimer tm(S_DCOMBINE, st);
-        launch_dcombine(D, dY, ws + L.Ys, plan->topk_w, plan->pos, ws + L.dYs, (float*)(ws + L.dl), st);
+        launch_dcombine(D, dY, ws + L.Ys, plan->topk_w, plan->pos, ws + L.dYs, (float*)(ws + L.dl),
+                        D.score_all ? (float*)(ws + L.gate_S) : nullptr, st);
         if ((s = check_launch("combine backward")) != MOE_OK) return s;
     }
 
@@ -357,7 +361,7 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     {
         ScopedTimer tm(S_GATEBWD, st);
         launch_gate_bwd(D, L, ws + L.Xs, ws + L.dXs, Wg, (const float*)(ws + L.dl), plan->topk_idx, plan->pos,
-                        plan->perm, plan->counts, plan->offsets, dX, dWg, dbg, ws, st);
+                        plan->perm, plan->counts, plan->offsets, dX, dWg, dbg, ws, D.score_all ? X : nullptr, st);
     }
     return check_launch("gate backward");
 }
@@ -420,8 +424,9 @@ moe_status_t moe_gather_backward(const moe_desc_t* desc, const moe_plan_t* plan,
     MOE_REQUIRE_PTR(Ys);
     MOE_REQUIRE_PTR(dYs);
     if (!dl || (reinterpret_cast<uintptr_t>(dl) & 3u)) { set_error("dl is NULL or not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    if (desc->score_all) { set_error("moe_gather_backward / moe_scatter_backward carry the gradient of the selected experts only (score_all must be 0)"); return MOE_ERR_UNSUPPORTED; }
     if (desc->N == 0) return MOE_OK;
-    launch_dcombine(*desc, dY, Ys, plan->topk_w, plan->pos, dYs, dl, (hipStream_t)stream);
+    launch_dcombine(*desc, dY, Ys, plan->topk_w, plan->pos, dYs, dl, nullptr, (hipStream_t)stream);
     return check_launch("gather backward");
 }
 
@@ -444,8 +449,9 @@ moe_status_t moe_scatter_backward(const moe_desc_t* desc, const moe_plan_t* plan
         MOE_REQUIRE_PTR(dX);
         if (!dl || (reinterpret_cast<uintptr_t>(dl) & 3u)) { set_error("dl is NULL or not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
     }
+    if (desc->score_all) { set_error("moe_gather_backward / moe_scatter_backward carry the gradient of the selected experts only (score_all must be 0)"); return MOE_ERR_UNSUPPORTED; }
     launch_gate_bwd(*desc, L, Xs, dXs, Wg, dl, plan->topk_idx, plan->pos, plan->perm, plan->counts, plan->offsets, dX,
-                    dWg, dbg, (char*)workspace, (hipStream_t)stream);
+                    dWg, dbg, (char*)workspace, nullptr, (hipStream_t)stream);
     return check_launch("scatter backward");
 }
 

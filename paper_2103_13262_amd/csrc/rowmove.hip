@@ -86,7 +86,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY, const void* __restrict__ Ys,
                                                      const float* __restrict__ topk_w,
                                                      const int32_t* __restrict__ pos, void* __restrict__ dYs,
-                                                     float* __restrict__ dl, long N, int k, int cpr)
+                                                     float* __restrict__ dl, long N, int k, int cpr,
+                                                     float* __restrict__ S_out)   // S_out: sum_i w_i dw_i per token, or NULL
 {
     constexpr int V = Vec<T>::N;
     const int lane = threadIdx.x & 63;
@@ -122,6 +123,7 @@ __global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY
 #pragma unroll
         for (int j = 0; j < kMaxK; ++j)
             if (j < k) dl[t * k + j] = w[j] * (dw[j] - s);
+        if (S_out) S_out[t] = s;
     }
 }
 
@@ -130,7 +132,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs, const void* __restrict__ WgT,
                                                    const float* __restrict__ dl, const int32_t* __restrict__ topk_idx,
                                                    const int32_t* __restrict__ pos, void* __restrict__ dX, long N, int k,
-                                                   int cpr)
+                                                   int cpr, const float* __restrict__ dxd)   // dxd: [N][d] float to add, or NULL
 {
     constexpr int V = Vec<T>::N;
     const long total = N * cpr;
@@ -153,6 +155,10 @@ __global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs,
             Vec<T>::load(WgT, (size_t)topk_idx[a] * cpr + c, wv);
 #pragma unroll
             for (int u = 0; u < V; ++u) acc[u] = fmaf(g, wv[u], acc[u]);
+        }
+        if (dxd) {
+#pragma unroll
+            for (int u = 0; u < V; ++u) acc[u] += dxd[(size_t)i * V + u];
         }
         Vec<T>::store(dX, (size_t)i, acc);
     }
@@ -245,7 +251,9 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
 template <typename G>
 __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part, const float* __restrict__ bpart,
                                                  const int32_t* __restrict__ P64, G* __restrict__ dWg,
-                                                 float* __restrict__ dbg, int d, int E, int accumulate)
+                                                 float* __restrict__ dbg, int d, int E, int accumulate,
+                                                 const float* __restrict__ dense_part,     // [nch][E][d] to add, or NULL
+                                                 const float* __restrict__ dense_bpart, int nch)
 {
     const int row = blockIdx.x * 256 + threadIdx.x, e = blockIdx.y;
     const int q1 = P64[e + 1];
@@ -258,6 +266,8 @@ __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part,
             s = (((s + a0) + a1) + a2) + a3;
         }
         for (; q < q1; ++q) s += part[(size_t)q * d + row];
+        if (dense_part)
+            for (int c = 0; c < nch; ++c) s += dense_part[((size_t)c * E + e) * d + row];
         const size_t i = (size_t)row * E + e;
         if constexpr (sizeof(G) == 2) {
             if (accumulate) s += bf16_to_f32(dWg[i]);
@@ -270,6 +280,8 @@ __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part,
     if (dbg && row == 0) {
         float s = 0.f;
         for (int q = P64[e]; q < q1; ++q) s += bpart[q];
+        if (dense_bpart)
+            for (int c = 0; c < nch; ++c) s += dense_bpart[(size_t)c * E + e];
         if (accumulate) s += dbg[e];
         dbg[e] = s;
     }
@@ -316,23 +328,33 @@ void launch_combine(const moe_desc_t& D, const void* Ys, const float* topk_w, co
 }
 
 void launch_dcombine(const moe_desc_t& D, const void* dY, const void* Ys, const float* topk_w,
-                     const int32_t* pos, void* dYs, float* dl, hipStream_t st)
+                     const int32_t* pos, void* dYs, float* dl, float* S_out, hipStream_t st)
 {
     const int cpr = (int)((size_t)D.d * dtype_size(D.dtype) / 16);
     const unsigned g = (unsigned)((D.N + 3) / 4);
     if (D.dtype == MOE_BF16)
         hipLaunchKernelGGL(dcombine_rows<unsigned short>, dim3(g), dim3(256), 0, st, dY, Ys, topk_w, pos, dYs, dl,
-                           (long)D.N, D.k, cpr);
+                           (long)D.N, D.k, cpr, S_out);
     else
         hipLaunchKernelGGL(dcombine_rows<float>, dim3(g), dim3(256), 0, st, dY, Ys, topk_w, pos, dYs, dl, (long)D.N,
-                           D.k, cpr);
+                           D.k, cpr, S_out);
 }
 
 void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, const void* dXs, const void* Wg,
                      const float* dl, const int32_t* topk_idx, const int32_t* pos, const int32_t* perm,
                      const int32_t* counts, const int32_t* offsets, void* dX, void* dWg, float* dbg, char* ws,
-                     hipStream_t st)
+                     const void* X_dense, hipStream_t st)
 {
+    // X_dense != NULL (scores over all experts): the experts that were not selected receive gradient too; their
+    // dense terms are computed first and added inside the kernels below that round dWg, dbg and dX.
+    const float *dpart = nullptr, *dbpart = nullptr, *dxd = nullptr;
+    if (X_dense) {
+        launch_gate_dense(D, L, X_dense, Wg, topk_idx, ws, st);
+        dpart = (const float*)(ws + L.dense_part);
+        dbpart = (const float*)(ws + L.dense_bpart);
+        if (D.N > 0) dxd = (const float*)(ws + L.dx_dense);
+    }
+    const int nch = D.N > 0 ? L.dense_chunks : 0;
     const int cpr = (int)((size_t)D.d * dtype_size(D.dtype) / 16);
     float* part = (float*)(ws + L.dwg_part);
     float* bpart = (float*)(ws + L.dbg_part);
@@ -347,20 +369,20 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
                            (const T*)Wg, (T*)WgT);
         if (D.grad_dtype == MOE_BF16)
             hipLaunchKernelGGL(dwg_final<unsigned short>, fg, dim3(256), 0, st, (const float*)part,
-                               (const float*)bpart, P64, (unsigned short*)dWg, dbg, D.d, D.E, D.accumulate);
+                               (const float*)bpart, P64, (unsigned short*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch);
         else
             hipLaunchKernelGGL(dwg_final<float>, fg, dim3(256), 0, st, (const float*)part, (const float*)bpart,
-                               P64, (float*)dWg, dbg, D.d, D.E, D.accumulate);
+                               P64, (float*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch);
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
-                           (long)D.N, D.k, cpr);
+                           (long)D.N, D.k, cpr, dxd);
     } else {
         using T = float;
         hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr,
                            (const T*)Wg, (T*)WgT);
         hipLaunchKernelGGL(dwg_final<float>, fg, dim3(256), 0, st, (const float*)part, (const float*)bpart,
-                           P64, (float*)dWg, dbg, D.d, D.E, D.accumulate);
+                           P64, (float*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch);
         hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
-                           (long)D.N, D.k, cpr);
+                           (long)D.N, D.k, cpr, dxd);
     }
 }
 

@@ -25,6 +25,7 @@ class Workload:
     zipf_s: float = 0.0   # 0: gate bias zero (near-uniform load); >0: expected load ~ (e+1)^-s
     seed: int = 0
     bias_std: float = 0.0  # > 0: the experts have biases b1[E,h], b2[E,d] ~ N(0, bias_std) (the five workloads have none)
+    score_all: bool = False  # scores = softmax over all experts instead of over the selected ones (ditto)
 
     @property
     def M(self):

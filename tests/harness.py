@@ -51,7 +51,7 @@ class GpuRun:
         self.torch, self.w, self.device = torch, w, device
         dt = B.MOE_BF16 if w.dtype == "bf16" else B.MOE_F32
         gd = dt if grad_dtype is None else grad_dtype
-        self.desc = B.make_desc(w.N, w.d, w.h, w.E, w.k, dt, gd, accumulate)
+        self.desc = B.make_desc(w.N, w.d, w.h, w.E, w.k, dt, gd, accumulate, 1 if w.score_all else 0)
         self.buf = B.MoeLayerBuffers(self.desc, device)
         tt = lambda n: to_torch(inputs[n], w.dtype, device)
         self.X, self.Wg, self.W1, self.W2 = tt("X"), tt("Wg"), tt("W1"), tt("W2")
@@ -127,7 +127,7 @@ def oracle_problem(w: Workload, inputs, dY=True):
     wide = lambda a: None if a is None else (orc.bf16_bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64))
     return orc.OracleProblem(inputs["X"], inputs["Wg"], inputs["W1"], inputs["W2"], w.k, bg=bg,
                              dY=inputs["dY"] if dY and "dY" in inputs else None, b1=wide(inputs.get("b1")),
-                             b2=wide(inputs.get("b2")))
+                             b2=wide(inputs.get("b2")), score_all=w.score_all)
 
 
 def check_plan_exact(run: GpuRun, inputs):
@@ -145,6 +145,6 @@ def check_plan_exact(run: GpuRun, inputs):
     np.testing.assert_array_equal(got["pos"], pos)
     np.testing.assert_array_equal(got["perm"], perm)
     np.testing.assert_allclose(got["w"], wt, rtol=0, atol=1e-6)
-    if w.k == 1:
+    if w.k == 1 and not w.score_all:
         assert np.all(got["w"] == 1.0)
     return dict(idx=idx, w=wt, counts=counts, offsets=offsets, pos=pos, perm=perm)

@@ -54,9 +54,10 @@ def test_workspace_size_and_regions():
     (dict(dtype=7), B.MOE_ERR_UNSUPPORTED),
     (dict(dtype=B.MOE_F32, grad_dtype=B.MOE_BF16), B.MOE_ERR_UNSUPPORTED),
     (dict(accumulate=2), B.MOE_ERR_INVALID_ARG),
+    (dict(score_all=2), B.MOE_ERR_INVALID_ARG),
 ])
 def test_bad_descriptions_are_rejected(kw, status):
-    base = dict(N=16, d=64, h=64, E=4, k=2, dtype=B.MOE_BF16, grad_dtype=None, accumulate=0)
+    base = dict(N=16, d=64, h=64, E=4, k=2, dtype=B.MOE_BF16, grad_dtype=None, accumulate=0, score_all=0)
     base.update(kw)
     d = B.make_desc(**base)
     assert B.moe_workspace_bytes(d) == 0
@@ -71,6 +72,17 @@ def test_reserved_fields_must_be_zero():
     d = B.make_desc(16, 64, 64, 4, 2)
     d.reserved[3] = 1
     assert B.moe_workspace_bytes(d) == 0
+
+
+def test_scores_over_all_experts_need_more_workspace_and_the_standalone_backwards_refuse_them():
+    a, b = B.make_desc(512, 64, 64, 8, 2), B.make_desc(512, 64, 64, 8, 2, score_all=1)
+    assert B.moe_workspace_bytes(b) >= B.moe_workspace_bytes(a) + 512 * 8 * 12 + 512 * 64 * 4
+    plan = B.make_plan(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    for c in (lambda: B.moe_gather_backward(b, plan, FAKE, FAKE, FAKE, FAKE),
+              lambda: B.moe_scatter_backward(b, plan, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, B.moe_workspace_bytes(b))):
+        with pytest.raises(B.MoeError) as ei:
+            c()
+        assert ei.value.status == B.MOE_ERR_UNSUPPORTED
 
 
 def test_null_misaligned_and_small_workspace_arguments():

@@ -36,6 +36,11 @@ CASES = [
     Workload("biases_f32", 220, 96, 160, 5, 2, "f32", 0.0, 27, 0.1),
     Workload("biases_bf16", 700, 128, 1024, 6, 2, "bf16", 0.7, 28, 0.1),
     Workload("biases_sparse_bf16", 40, 64, 96, 48, 2, "bf16", 0.0, 29, 0.1),
+    # scores = softmax over all experts (every expert's gate column receives gradient, also with top-1)
+    Workload("scores_all_f32", 180, 96, 64, 5, 2, "f32", 0.0, 33, 0.0, True),
+    Workload("scores_all_top1_bf16", 600, 128, 256, 12, 1, "bf16", 0.5, 34, 0.0, True),
+    Workload("scores_all_wide_bf16", 300, 160, 64, 70, 3, "bf16", 0.0, 35, 0.1, True),
+    Workload("scores_all_24_experts_f32", 1100, 64, 64, 24, 2, "f32", 0.0, 36, 0.0, True),
     # the limits of the description: 1024 experts with top-8, and a batch of many plan chunks
     Workload("max_experts_top8_bf16", 300, 64, 32, 1024, 8, "bf16", 0.0, 30),
     Workload("many_tokens_f32", 70000, 32, 32, 6, 2, "f32", 0.6, 31),
@@ -121,7 +126,7 @@ def _full_check(w, grad_dtype=None):
         assert not np.any(to_numpy64(run.dW1[e])) and not np.any(to_numpy64(run.dW2[e]))
         if w.bias_std > 0.0:
             assert not np.any(to_numpy64(run.db1[e])) and not np.any(to_numpy64(run.db2[e]))
-    if w.k == 1:                        # softmax over one logit: no gradient reaches the gate
+    if w.k == 1 and not w.score_all:    # softmax over one logit: no gradient reaches the gate
         assert not np.any(run.region("dl")) and not np.any(to_numpy64(run.dWg)) and not np.any(to_numpy64(run.dbg)[:w.E])
     return run, inputs, ref
 

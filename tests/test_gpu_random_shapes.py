@@ -1,7 +1,7 @@
 """Parity on seeded random shapes: the grouped products choose between whole tiles in rounds, tiles cut by rows and
 tiles cut along the reduction from the tile counts, and the weight gradients between two ways of dealing tiles to
 the XCDs, so a spread of shapes (expert counts that are no multiple of 8, reductions of 32 to 3072, skewed and
-near-empty experts, top-1 to top-4) walks through combinations that the named cases do not."""
+near-empty experts, top-1 to top-4, with and without expert biases, both score modes) walks through combinations that the named cases do not."""
 import numpy as np
 import pytest
 
@@ -24,7 +24,7 @@ def _shapes():
         N = int(max(1, min(2500, g.integers(1, max(2, int(budget))))))
         zipf = float(g.choice([0.0, 0.0, 0.8, 1.5]))
         dtype = "bf16" if i % 5 else "f32"
-        out.append(Workload(f"rand{i}", N, d, h, E, k, dtype, zipf, 9000 + i, 0.1 if i % 3 == 0 else 0.0))
+        out.append(Workload(f"rand{i}", N, d, h, E, k, dtype, zipf, 9000 + i, 0.1 if i % 3 == 0 else 0.0, i % 4 == 1))
     return out
 
 
