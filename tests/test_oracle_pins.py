@@ -479,3 +479,28 @@ def test_gather_gradients_match_central_differences():
         b[i] -= eps
         numl[i] = (loss(Ys, a) - loss(Ys, b)) / (2 * eps)
     np.testing.assert_allclose(dl, numl, rtol=1e-6, atol=1e-8)
+
+
+# ------------------------------------------------------------------ load-balance monitor
+def test_balance_stats_closed_forms_and_library_softmax():
+    from oracle.moe_balance import balance_stats
+
+    g = np.random.default_rng(5)
+    N, E, k = 40, 6, 2
+    logits = g.standard_normal((N, E))
+    idx = np.argsort(-logits, axis=1, kind="stable")[:, :k]
+    frac, prob, loss = balance_stats(logits, idx, E)
+    np.testing.assert_allclose(frac, np.bincount(idx.reshape(-1), minlength=E) / (N * k), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(prob, softmax(logits, axis=1).mean(0), rtol=1e-13)
+    assert abs(frac.sum() - 1) < 1e-14 and abs(prob.sum() - 1) < 1e-14
+    np.testing.assert_allclose(loss, E * (frac * prob).sum(), rtol=1e-14)
+    # a gate that cannot tell the experts apart: every probability is 1/E and the scalar is 1 whatever the routing
+    _, p0, l0 = balance_stats(np.zeros((N, E)), idx, E)
+    np.testing.assert_allclose(p0, 1.0 / E, rtol=1e-15)
+    assert abs(l0 - 1.0) < 1e-14
+    # a gate that sends everything to one expert with certainty: the scalar is E
+    hot = np.full((N, E), -50.0)
+    hot[:, 3] = 50.0
+    f1, p1, l1 = balance_stats(hot, np.full((N, 1), 3), E)
+    assert f1[3] == 1.0 and abs(p1[3] - 1.0) < 1e-12 and abs(l1 - E) < 1e-10
+
