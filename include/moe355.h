@@ -72,7 +72,9 @@ typedef struct {
                            selected experts (Algorithm 1 read literally with a softmax gate:
                            they sum to less than 1, and every expert's gate column, selected or
                            not, receives gradient - also with k = 1)                           */
-    int32_t reserved[7]; /* must be zero                                                      */
+    int32_t balance_stats; /* 1: moe_plan keeps what moe_balance_stats needs (the gate logits) in the
+                           workspace; implied by score_all                                     */
+    int32_t reserved[6]; /* must be zero                                                      */
 } moe_desc_t;
 
 /* Routing of one batch; six caller-owned device arrays that moe_plan fills and
@@ -134,6 +136,20 @@ moe_status_t moe_forward(const moe_desc_t *desc, const moe_plan_t *plan, const v
 moe_status_t moe_backward(const moe_desc_t *desc, const moe_plan_t *plan, const void *X, const void *Wg,
                           const void *W1, const void *W2, const void *dY, void *dX, void *dWg, float *dbg,
                           void *dW1, void *dW2, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Load-balance monitor of the batch routed by the last moe_plan on this workspace (the paper leaves
+ * a load-balance monitor to future work, Section 6; these are the statistics one is built from).
+ * Needs desc->balance_stats or desc->score_all.
+ *   fraction  device [E] float: counts[e] / (N k), the share of the assignments expert e received
+ *   mean_prob device [E] float: mean over the tokens of softmax(x W_g + b_g)[e]
+ *   loss      device [1] float: E * sum_e fraction[e] mean_prob[e]  (1 for a gate that cannot tell
+ *             the experts apart, E when one expert gets everything with certainty); any may be NULL.
+ * Sums run in a fixed order.  With N == 0 the outputs are zeros.
+ */
+moe_status_t moe_balance_stats(const moe_desc_t *desc, const moe_plan_t *plan, float *fraction,
+                               float *mean_prob, float *loss, void *workspace, size_t workspace_bytes,
+                               void *stream);
 
 /*
  * Gradients of the expert biases (only needed when moe_forward was given b1 / b2; the other

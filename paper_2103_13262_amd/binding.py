@@ -13,14 +13,14 @@ LIB_PATH = os.path.join(_HERE, "libmoe355.so")
 MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP = 0, -1, -2, -3, -4
 MOE_F32, MOE_BF16 = 0, 1
 EXPORTS = ("moe_workspace_bytes", "moe_workspace_region", "moe_plan", "moe_forward", "moe_backward",
-           "moe_bias_backward", "moe_scatter", "moe_gather", "moe_gather_backward", "moe_scatter_backward",
+           "moe_bias_backward", "moe_balance_stats", "moe_scatter", "moe_gather", "moe_gather_backward", "moe_scatter_backward",
            "moe_last_error", "moe_profile_enable", "moe_profile_read")
 
 
 class MoeDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("d", C.c_int32), ("h", C.c_int32), ("E", C.c_int32), ("k", C.c_int32),
                 ("dtype", C.c_int32), ("grad_dtype", C.c_int32), ("accumulate", C.c_int32),
-                ("score_all", C.c_int32), ("reserved", C.c_int32 * 7)]
+                ("score_all", C.c_int32), ("balance_stats", C.c_int32), ("reserved", C.c_int32 * 6)]
 
 
 class MoePlan(C.Structure):
@@ -95,8 +95,8 @@ def _check(status):
         raise MoeError(status, lib().moe_last_error().decode())
 
 
-def make_desc(N, d, h, E, k, dtype=MOE_BF16, grad_dtype=None, accumulate=0, score_all=0):
-    return MoeDesc(N, d, h, E, k, dtype, dtype if grad_dtype is None else grad_dtype, accumulate, score_all)
+def make_desc(N, d, h, E, k, dtype=MOE_BF16, grad_dtype=None, accumulate=0, score_all=0, balance_stats=0):
+    return MoeDesc(N, d, h, E, k, dtype, dtype if grad_dtype is None else grad_dtype, accumulate, score_all, balance_stats)
 
 
 def moe_workspace_bytes(desc):
@@ -150,6 +150,11 @@ def moe_backward(desc, plan, X, Wg, W1, W2, dY, dX, dWg, dbg, dW1, dW2, workspac
 def moe_bias_backward(desc, plan, db1, db2, workspace, workspace_bytes, stream=0):
     _check(lib().moe_bias_backward(C.byref(desc), None if plan is None else C.byref(plan), _p(db1), _p(db2), _p(workspace),
                                    C.c_size_t(workspace_bytes), C.c_void_p(stream)))
+
+
+def moe_balance_stats(desc, plan, fraction, mean_prob, loss, workspace, workspace_bytes, stream=0):
+    _check(lib().moe_balance_stats(C.byref(desc), None if plan is None else C.byref(plan), _p(fraction), _p(mean_prob),
+                                   _p(loss), _p(workspace), C.c_size_t(workspace_bytes), C.c_void_p(stream)))
 
 
 def moe_scatter(desc, plan, X, Xs, stream=0):

@@ -27,9 +27,11 @@ struct WsLayout {
     size_t dwg_part;  // [pieces][d] float: partial sums of dWg over pieces of 64 rows
     size_t dbg_part;  // [pieces] float
     size_t bias_part; // [pieces][max(d,h)] float: partial column sums for the expert-bias gradients
-    // only with desc.score_all (scores = softmax over all experts):
+    // only with desc.score_all or desc.balance_stats:
     size_t logits;    // [N][E] double: the gate logits
     size_t lse;       // [N] double: log of the sum of exp of a token's logits
+    size_t prob_part; // [ceil(N/512)][E] double: sums of the gate probabilities by chunk of 512 tokens
+    // only with desc.score_all (scores = softmax over all experts):
     size_t gate_S;    // [N] float: sum_j w_j dL/dw_j of a token
     size_t gate_R;    // [N][E] float: dL/dlogit of the experts that were not selected (0 at the selected ones)
     size_t dx_dense;  // [N][d] float: their contribution to dX
@@ -74,9 +76,12 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.bias_part = take((size_t)L.dwg_pieces * (D.d > D.h ? D.d : D.h) * sizeof(float));
     L.WgT = take((size_t)D.E * D.d * b);
     L.dense_chunks = (D.N + 511) / 512;
-    if (D.score_all) {
+    if (D.score_all || D.balance_stats) {
         L.logits = take((size_t)D.N * D.E * sizeof(double));
         L.lse = take((size_t)D.N * sizeof(double));
+        L.prob_part = take((size_t)(L.dense_chunks > 0 ? L.dense_chunks : 1) * D.E * sizeof(double));
+    }
+    if (D.score_all) {
         L.gate_S = take((size_t)D.N * sizeof(float));
         L.gate_R = take((size_t)D.N * D.E * sizeof(float));
         L.dx_dense = take((size_t)D.N * D.d * sizeof(float));
@@ -111,6 +116,8 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
                      const float* dl, const int32_t* topk_idx, const int32_t* pos, const int32_t* perm,
                      const int32_t* counts, const int32_t* offsets, void* dX, void* dWg, float* dbg, char* ws,
                      const void* X_dense, hipStream_t st);
+void launch_balance_stats(const moe_desc_t& D, const WsLayout& L, const int32_t* counts, float* fraction, float* mean_prob,
+                          float* loss, char* ws, hipStream_t st);
 void launch_gate_dense(const moe_desc_t& D, const WsLayout& L, const void* X, const void* Wg, const int32_t* topk_idx,
                        char* ws, hipStream_t st);
 

@@ -122,6 +122,56 @@ __global__ __launch_bounds__(256) void dense_dx(const float* __restrict__ R, con
     }
 }
 
+// ---- load-balance monitor: share of the assignments and mean gate probability of every expert ----------------
+// grid (chunks of 512 tokens, ceil(E / 256)): psum[c][e] = sum over the chunk's tokens, in ascending order, of
+// exp(l[t][e] - lse[t]).
+__global__ __launch_bounds__(256) void balance_partial(const double* __restrict__ logits, const double* __restrict__ lse,
+                                                       long N, int E, double* __restrict__ psum)
+{
+    const int c = blockIdx.x, e = blockIdx.y * 256 + threadIdx.x;
+    if (e >= E) return;
+    const long t1 = min((long)(c + 1) * 512, N);
+    double s = 0.0;
+    for (long t = (long)c * 512; t < t1; ++t) s += exp(logits[(size_t)t * E + e] - lse[t]);
+    psum[(size_t)c * E + e] = s;
+}
+
+// one workgroup: the chunks in ascending order per expert, then the scalar over the experts in ascending order
+__global__ __launch_bounds__(1024) void balance_final(const double* __restrict__ psum, const int32_t* __restrict__ counts,
+                                                      long N, int E, int k, int nch, float* __restrict__ fraction,
+                                                      float* __restrict__ mean_prob, float* __restrict__ loss)
+{
+    __shared__ double s_term[kMaxE];
+    const int e = threadIdx.x;
+    if (e < E) {
+        double p = 0.0;
+        for (int c = 0; c < nch; ++c) p += psum[(size_t)c * E + e];
+        p = N > 0 ? p / (double)N : 0.0;
+        const double f = N > 0 ? (double)counts[e] / ((double)N * k) : 0.0;
+        if (fraction) fraction[e] = (float)f;
+        if (mean_prob) mean_prob[e] = (float)p;
+        s_term[e] = f * p;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && loss) {
+        double s = 0.0;
+        for (int i = 0; i < E; ++i) s += s_term[i];
+        *loss = (float)(s * E);
+    }
+}
+
+void launch_balance_stats(const moe_desc_t& D, const WsLayout& L, const int32_t* counts, float* fraction, float* mean_prob,
+                          float* loss, char* ws, hipStream_t st)
+{
+    double* psum = (double*)(ws + L.prob_part);
+    const int nch = D.N > 0 ? L.dense_chunks : 0;
+    if (nch > 0)
+        hipLaunchKernelGGL(balance_partial, dim3((unsigned)nch, (unsigned)((D.E + 255) / 256)), dim3(256), 0, st,
+                           (const double*)(ws + L.logits), (const double*)(ws + L.lse), (long)D.N, D.E, psum);
+    hipLaunchKernelGGL(balance_final, dim3(1), dim3(1024), 0, st, (const double*)psum, counts, (long)D.N, D.E, D.k, nch,
+                       fraction, mean_prob, loss);
+}
+
 void launch_gate_dense(const moe_desc_t& D, const WsLayout& L, const void* X, const void* Wg, const int32_t* topk_idx,
                        char* ws, hipStream_t st)
 {

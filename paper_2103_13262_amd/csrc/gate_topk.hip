@@ -524,12 +524,12 @@ static void launch_mfma(const moe_desc_t& D, const T* X, const T* Wg, const floa
     else launch_wide_mt<T, 1>(D, X, WgT, bg, idx, w, logits, st);
 }
 
-// Scores = softmax over all E logits, taken at the selected experts: one wavefront per token sums exp(l - top)
-// over the stored logits (lanes stride the experts, then a fixed butterfly), rewrites the k scores and keeps
-// log-sum-exp for the backward pass.
+// One wavefront per token sums exp(l - top) over the stored logits (lanes stride the experts, then a fixed
+// butterfly) and keeps log-sum-exp for the backward pass and the load-balance monitor; with scores taken from the
+// softmax over all E logits (rewrite) it also replaces the k scores.
 __global__ __launch_bounds__(256) void gate_scores_all(const double* __restrict__ logits, const int32_t* __restrict__ topk_idx,
                                                        int N, int E, int k, float* __restrict__ topk_w,
-                                                       double* __restrict__ lse)
+                                                       double* __restrict__ lse, int rewrite)
 {
     const int lane = threadIdx.x & 63;
     const long t = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -539,7 +539,7 @@ __global__ __launch_bounds__(256) void gate_scores_all(const double* __restrict_
     double s = 0.0;
     for (int e = lane; e < E; e += 64) s += exp(l[e] - top);
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (lane < k) topk_w[t * k + lane] = (float)(exp(l[topk_idx[t * k + lane]] - top) / s);
+    if (rewrite && lane < k) topk_w[t * k + lane] = (float)(exp(l[topk_idx[t * k + lane]] - top) / s);
     if (lane == 0) lse[t] = top + log(s);
 }
 
@@ -557,7 +557,7 @@ void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const 
     }
     if (logits)
         hipLaunchKernelGGL(gate_scores_all, dim3((unsigned)((D.N + 3) / 4)), dim3(256), 0, st, (const double*)logits,
-                           (const int32_t*)topk_idx, D.N, D.E, D.k, topk_w, lse);
+                           (const int32_t*)topk_idx, D.N, D.E, D.k, topk_w, lse, D.score_all);
 }
 
 }  // namespace moe

@@ -89,7 +89,8 @@ static moe_status_t check_desc(const moe_desc_t* D)
     if (D->E > kMaxE) { set_error("E=%d exceeds %d", D->E, kMaxE); return MOE_ERR_UNSUPPORTED; }
     if (D->k > kMaxK) { set_error("k=%d exceeds %d", D->k, kMaxK); return MOE_ERR_UNSUPPORTED; }
     if (D->score_all != 0 && D->score_all != 1) { set_error("score_all must be 0 or 1"); return MOE_ERR_INVALID_ARG; }
-    for (int i = 0; i < 7; ++i)
+    if (D->balance_stats != 0 && D->balance_stats != 1) { set_error("balance_stats must be 0 or 1"); return MOE_ERR_INVALID_ARG; }
+    for (int i = 0; i < 6; ++i)
         if (D->reserved[i]) { set_error("reserved[%d] must be 0", i); return MOE_ERR_UNSUPPORTED; }
     const long long M = (long long)D->N * D->k;
     if (M > 0x7fffffffLL || M * (long long)(D->d > D->h ? D->d : D->h) > (1LL << 46)) {
@@ -222,8 +223,8 @@ moe_status_t moe_plan(const moe_desc_t* desc, const void* X, const void* Wg, con
     if (D.N > 0) {
         ScopedTimer tm(S_GATE, st);
         launch_gate_topk(D, X, Wg, bg, plan->topk_idx, plan->topk_w, (char*)workspace + L.WgT,
-                         D.score_all ? (double*)((char*)workspace + L.logits) : nullptr,
-                         D.score_all ? (double*)((char*)workspace + L.lse) : nullptr, st);
+                         (D.score_all || D.balance_stats) ? (double*)((char*)workspace + L.logits) : nullptr,
+                         (D.score_all || D.balance_stats) ? (double*)((char*)workspace + L.lse) : nullptr, st);
         if ((s = check_launch("gate/top-k")) != MOE_OK) return s;
     }
     // With N == 0 the plan kernels still run: they write counts = 0, offsets = 0 and empty tile tables.
@@ -364,6 +365,25 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
                         plan->perm, plan->counts, plan->offsets, dX, dWg, dbg, ws, D.score_all ? X : nullptr, st);
     }
     return check_launch("gate backward");
+}
+
+moe_status_t moe_balance_stats(const moe_desc_t* desc, const moe_plan_t* plan, float* fraction, float* mean_prob,
+                               float* loss, void* workspace, size_t workspace_bytes, void* stream)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if ((s = check_plan(plan)) != MOE_OK) return s;
+    if (!desc->balance_stats && !desc->score_all) {
+        set_error("moe_balance_stats needs desc.balance_stats or desc.score_all (moe_plan keeps the gate logits only then)");
+        return MOE_ERR_UNSUPPORTED;
+    }
+    for (const float* p : {fraction, mean_prob, loss})
+        if (p && (reinterpret_cast<uintptr_t>(p) & 3u)) { set_error("output is not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
+    WsLayout L;
+    if ((s = check_ws(desc, workspace, workspace_bytes, &L)) != MOE_OK) return s;
+    launch_balance_stats(*desc, L, plan->counts, fraction, mean_prob, loss, (char*)workspace, (hipStream_t)stream);
+    return check_launch("balance statistics");
 }
 
 moe_status_t moe_bias_backward(const moe_desc_t* desc, const moe_plan_t* plan, float* db1, float* db2, void* workspace,

@@ -55,9 +55,10 @@ def test_workspace_size_and_regions():
     (dict(dtype=B.MOE_F32, grad_dtype=B.MOE_BF16), B.MOE_ERR_UNSUPPORTED),
     (dict(accumulate=2), B.MOE_ERR_INVALID_ARG),
     (dict(score_all=2), B.MOE_ERR_INVALID_ARG),
+    (dict(balance_stats=3), B.MOE_ERR_INVALID_ARG),
 ])
 def test_bad_descriptions_are_rejected(kw, status):
-    base = dict(N=16, d=64, h=64, E=4, k=2, dtype=B.MOE_BF16, grad_dtype=None, accumulate=0, score_all=0)
+    base = dict(N=16, d=64, h=64, E=4, k=2, dtype=B.MOE_BF16, grad_dtype=None, accumulate=0, score_all=0, balance_stats=0)
     base.update(kw)
     d = B.make_desc(**base)
     assert B.moe_workspace_bytes(d) == 0

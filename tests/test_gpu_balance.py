@@ -1,0 +1,64 @@
+"""Load-balance monitor on the GPU against its definition (oracle/moe_balance.py): the share of the assignments and
+the mean gate probability of every expert, and the scalar made of them."""
+import numpy as np
+import pytest
+
+from harness import GpuRun, oracle_problem
+from paper_2103_13262_amd import binding as B
+from paper_2103_13262_amd.synth import Workload, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    Workload("balance_f32", 700, 96, 64, 5, 2, "f32", 0.8, 81),
+    Workload("balance_bf16", 1500, 128, 64, 16, 2, "bf16", 0.0, 82),
+    Workload("balance_wide_bf16", 300, 64, 32, 300, 3, "bf16", 1.2, 83),
+    Workload("balance_scores_all_bf16", 520, 64, 64, 24, 1, "bf16", 0.5, 84, 0.0, True),
+]
+
+
+@pytest.mark.parametrize("w", CASES, ids=lambda w: w.name)
+def test_balance_stats_match_their_definition(w):
+    import oracle as orc
+    import torch
+    from oracle.moe_balance import balance_stats
+
+    inputs = make_inputs(w)
+    run = GpuRun(w, inputs)
+    run.desc = B.make_desc(w.N, w.d, w.h, w.E, w.k, run.desc.dtype, run.desc.grad_dtype, 0, 1 if w.score_all else 0, 1)
+    run.buf = B.MoeLayerBuffers(run.desc, run.device)
+    run.plan()
+    frac = torch.full((w.E,), float("nan"), dtype=torch.float32, device=run.device)
+    prob = torch.full((w.E,), float("nan"), dtype=torch.float32, device=run.device)
+    loss = torch.full((1,), float("nan"), dtype=torch.float32, device=run.device)
+    b = run.buf
+    B.moe_balance_stats(run.desc, b.plan, frac, prob, loss, b.workspace, b.ws_bytes, b.stream())
+    torch.cuda.synchronize()
+    idx, _, logits = orc.gate(oracle_problem(w, inputs, dY=False))
+    f, p, l = balance_stats(logits, idx, w.E)
+    np.testing.assert_array_equal(frac.cpu().numpy(), f.astype(np.float32))          # ratios of exact counts
+    np.testing.assert_allclose(prob.cpu().numpy(), p, rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(float(loss.cpu()[0]), l, rtol=2e-6)
+    assert abs(float(prob.sum().cpu()) - 1.0) < 1e-5
+
+
+def test_balance_stats_need_the_flag_and_accept_an_empty_batch():
+    import torch
+
+    w = Workload("noflag", 64, 64, 64, 4, 2, "bf16", 0.0, 85)
+    run = GpuRun(w, make_inputs(w))
+    run.plan()
+    out = torch.zeros(4, dtype=torch.float32, device=run.device)
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_balance_stats(run.desc, run.buf.plan, out, out, None, run.buf.workspace, run.buf.ws_bytes, run.buf.stream())
+    assert ei.value.status == B.MOE_ERR_UNSUPPORTED
+    d0 = B.make_desc(0, 64, 64, 4, 2, balance_stats=1)
+    buf = B.MoeLayerBuffers(d0, run.device)
+    X = torch.zeros((1, 64), dtype=torch.bfloat16, device=run.device)
+    B.moe_plan(d0, X, run.Wg, None, buf.plan, buf.workspace, buf.ws_bytes, buf.stream())
+    f = torch.full((4,), float("nan"), dtype=torch.float32, device=run.device)
+    p = torch.full((4,), float("nan"), dtype=torch.float32, device=run.device)
+    l = torch.full((1,), float("nan"), dtype=torch.float32, device=run.device)
+    B.moe_balance_stats(d0, buf.plan, f, p, l, buf.workspace, buf.ws_bytes, buf.stream())
+    torch.cuda.synchronize()
+    assert not f.any() and not p.any() and float(l[0]) == 0.0
