@@ -13,7 +13,7 @@
  * imported or called by the product path: only tests, the smoke check and the
  * cpu_baseline leg of the benchmark use it.
  *
- * Readings taken where the paper is silent (all restated in the design notes):
+ * Readings taken where the paper is silent:
  *   - G(x) is one fully-connected layer: l = x W_g + b_g (Section 5.2).
  *   - ArgMax_k ranks the raw logits; equal logits go to the lower expert id;
  *     slot j holds the j-th largest.
