@@ -86,8 +86,7 @@ def _full_check(w, grad_dtype=None):
     errs["Y"] = rel_err(to_numpy64(run.Y)[:w.N], ref["Y"])
     errs["dl"] = rel_err(run.region("dl"), ref["dl"].reshape(-1))
     errs["dX"] = rel_err(to_numpy64(run.dX)[:w.N], ref["dX"])
-    errs["dbg"] = rel_err(to_numpy64(run.dbg)[:w.E], ref["dbg"])
-    # Per-expert gradients (dW1, dW2, the expert's column of dWg, its rows of db1 / db2) are judged expert by expert,
+    # Per-expert gradients (dW1, dW2, the expert's column of dWg and entry of dbg, its rows of db1 / db2) are judged expert by expert,
     # each against the RMS of the whole tensor or of the expert's own part, whichever is larger: under a skewed
     # load the part of the largest expert has several times the RMS of the whole tensor, its rounding errors scale
     # with its own size, and an exact-sum computation from bf16-stored H, dYs, dZ, Ys already reaches 3-4e-2 of
@@ -98,7 +97,7 @@ def _full_check(w, grad_dtype=None):
     # is held to twice the bound and the stated bound is applied to max|err| / max|ref| of the part.
     counts = ref_plan["counts"]
     per_expert = [("dW1", to_numpy64(run.dW1), ref["dW1"]), ("dW2", to_numpy64(run.dW2), ref["dW2"]),
-                  ("dWg", to_numpy64(run.dWg).T, ref["dWg"].T)]
+                  ("dWg", to_numpy64(run.dWg).T, ref["dWg"].T), ("dbg", to_numpy64(run.dbg)[:w.E, None], ref["dbg"][:, None])]
     if w.bias_std > 0.0:                # expert-bias gradients (fp32 sums of the stored dZ and dYs rows)
         per_expert += [("db1", to_numpy64(run.db1), ref["db1"]), ("db2", to_numpy64(run.db2), ref["db2"])]
     for name, got, want in per_expert:
@@ -108,10 +107,10 @@ def _full_check(w, grad_dtype=None):
             err = rel_err(got[e], want[e], rms=max(rms, float(np.sqrt(np.mean(want[e] ** 2)))))
             if w.dtype == "bf16" and 0 < counts[e] < 64:
                 worst_few = max(worst_few, err)
-                # (not for dWg: a column of an expert with one or two rows is dl * x, and a single dl that is small
+                # (not for dWg and dbg: a column of an expert with one or two rows is dl * x, its dbg entry dl itself, and a single dl that is small
                 # against the others - it is a difference of the dw - has no relative accuracy to speak of; dl is
                 # judged as a vector above)
-                if name != "dWg":
+                if name not in ("dWg", "dbg"):
                     assert max_err_over_max(got[e], want[e]) <= tol, (name, e, int(counts[e]))
             else:
                 worst_many = max(worst_many, err)
