@@ -153,6 +153,8 @@ struct GemmArgs {
     int32_t* sk_error;
     const int32_t* by_expert;  // 1: the weight-gradient products give every XCD whole experts (decided by the plan step)
     long long* clock_probe;    // [2]: shader cycles and 100 MHz ticks of workgroup 0 of the last launch
+    const int32_t* skewed;     // 1: the experts' sizes are strongly skewed (decided by the plan step)
+    int32_t* dyn_counters;     // [9]: next tile of every XCD's list and the number of workgroups that have finished; zero between launches
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT
     long long* trace; // development builds only: per-workgroup phase times (8 words per workgroup) or NULL

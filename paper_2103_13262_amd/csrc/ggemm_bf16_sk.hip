@@ -204,6 +204,8 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     long dp_i, dp_stride;            // next whole-tile item and the stride to the one after
     int tpe = 0, per = 0;            // weight gradients: tiles per expert, and per expert and XCD
     bool by_expert = false;          // weight gradients: every XCD works on whole experts (decided by the plan step)
+    bool dynamic = false;            // weight gradients: tiles are taken from a per-XCD counter instead of in rounds
+    __shared__ int s_next;
     if constexpr (KIND != kColsT) {
         const long T = (long)P[g.E] * ntn;
         const long base = T >> 3;
@@ -221,6 +223,10 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         if (by_expert) { n_dp = (long)((g.E + 7) / 8) * tpe; dp_i = wj; dp_stride = W; }
         else if ((tpe & 7) == 0) { per = tpe >> 3; n_dp = (long)g.E * per; dp_i = wj; dp_stride = W; }
         else { n_dp = (long)g.E * tpe; dp_i = blockIdx.x; dp_stride = gridDim.x; }
+        // With fewer tiles per expert and XCD than workgroups, a round of tiles spans several experts; when their
+        // sizes are strongly skewed, fixed rounds leave the workgroups that got the largest experts' tiles far
+        // behind.  Then the XCD's list (longest reductions first) is handed out on demand from a counter.
+        dynamic = !by_expert && per > 0 && per < W && *g.skewed != 0;
     }
 
     // Tile number L (rows kinds) -> expert, row block inside the expert, column block.  Order inside an expert:
@@ -313,6 +319,17 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
             // rank r goes to XCD r%8, every other group of eight reversed - so that each operand panel is fetched
             // into one L2 only; otherwise an eighth of every expert's tiles.
             int ord, q;
+            if (dynamic) {
+                // (agent-scope atomic: correct wherever the workgroups run; which tile a workgroup computes does not
+                // change the tile's value, so results stay bit-for-bit repeatable)
+                if (tid == 0) s_next = __hip_atomic_fetch_add(g.dyn_counters + xcd, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __syncthreads();
+                const long item = s_next;
+                __syncthreads();                  // every wave has read it before the next fetch overwrites it
+                if (item >= n_dp) return false;
+                ord = (int)(item / per);
+                q = xcd * per + (int)(item - (long)ord * per);
+            } else
             for (;;) {
                 const long round = dp_i / dp_stride, lanepos = dp_i - round * dp_stride;
                 const long item = round * dp_stride + ((round & 1) ? dp_stride - 1 - lanepos : lanepos);
@@ -764,6 +781,13 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
 #ifdef MOE355_DEV_TRACE
         ++tr_items;
 #endif
+    }
+    if constexpr (KIND == kColsT) {
+        if (dynamic && tid == 0) {       // the last workgroup to finish leaves the counters at zero for the next launch
+            const int done = __hip_atomic_fetch_add(g.dyn_counters + 8, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (done == (int)gridDim.x - 1)
+                for (int i = 0; i < 9; ++i) __hip_atomic_store(g.dyn_counters + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     if (blockIdx.x == 0 && tid == 0) {   // shader cycles and 100 MHz ticks this workgroup lived: the clock the launch ran at
         g.clock_probe[0] = clock64() - probe_cycles0;

@@ -272,6 +272,8 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     a.sk_error = (int32_t*)(ws + L.sk_error);
     a.by_expert = (const int32_t*)(ws + L.sk_error) + 1;
     a.clock_probe = (long long*)(ws + L.sk_error + 8);
+    a.skewed = (const int32_t*)(ws + L.sk_error) + 6;
+    a.dyn_counters = (int32_t*)(ws + L.sk_error + 32);
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
     a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h; a.bias = b1;
@@ -333,6 +335,8 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     a.sk_error = (int32_t*)(ws + L.sk_error);
     a.by_expert = (const int32_t*)(ws + L.sk_error) + 1;
     a.clock_probe = (long long*)(ws + L.sk_error + 8);
+    a.skewed = (const int32_t*)(ws + L.sk_error) + 6;
+    a.dyn_counters = (int32_t*)(ws + L.sk_error + 32);
     a.out_f32 = D.grad_dtype == MOE_F32;
     a.accumulate = D.accumulate;
 

@@ -143,6 +143,11 @@ __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ id
         int mx = 0, sum = 0;
         for (int x = 0; x < 8; ++x) { mx = max(mx, s_xcd[x]); sum += s_xcd[x]; }
         zeros[kZeroedBytes / 4 - 63] = (E >= 8 && (long)mx * 80 <= (long)sum * 11) ? 1 : 0;
+        // Strongly skewed sizes (largest expert above three times the mean): the weight-gradient products hand out
+        // their tiles on demand instead of in fixed rounds; the flag sits five words behind the one above.
+        int big = 0;
+        for (int i = 0; i < E; ++i) big = max(big, s_cnt[i]);
+        zeros[kZeroedBytes / 4 - 58] = (E >= 2 && (long)big * E > 3 * M) ? 1 : 0;
     }
 }
 
