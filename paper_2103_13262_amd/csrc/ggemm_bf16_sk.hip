@@ -205,6 +205,7 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     int tpe = 0, per = 0;            // weight gradients: tiles per expert, and per expert and XCD
     bool by_expert = false;          // weight gradients: every XCD works on whole experts (decided by the plan step)
     bool dynamic = false;            // weight gradients: tiles are taken from a per-XCD counter instead of in rounds
+    int32_t* dyn_ctr = nullptr;      // this workgroup's counter (one per XCD, or one for all when tiles are not split by XCD)
     __shared__ int s_next;
     if constexpr (KIND != kColsT) {
         const long T = (long)P[g.E] * ntn;
@@ -223,10 +224,12 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         if (by_expert) { n_dp = (long)((g.E + 7) / 8) * tpe; dp_i = wj; dp_stride = W; }
         else if ((tpe & 7) == 0) { per = tpe >> 3; n_dp = (long)g.E * per; dp_i = wj; dp_stride = W; }
         else { n_dp = (long)g.E * tpe; dp_i = blockIdx.x; dp_stride = gridDim.x; }
-        // With fewer tiles per expert and XCD than workgroups, a round of tiles spans several experts; when their
-        // sizes are strongly skewed, fixed rounds leave the workgroups that got the largest experts' tiles far
-        // behind.  Then the XCD's list (longest reductions first) is handed out on demand from a counter.
-        dynamic = !by_expert && per > 0 && per < W && *g.skewed != 0;
+        // A round of tiles can span several experts; when their sizes are strongly skewed, fixed rounds leave the
+        // workgroups that got the largest experts' tiles far behind.  Then the list (longest reductions first)
+        // is handed out on demand from a counter.
+        // (with a whole round inside one expert the fixed rounds are balanced already)
+        dynamic = !by_expert && (per == 0 || per < W) && *g.skewed != 0;
+        dyn_ctr = g.dyn_counters + (per ? xcd : 0);
     }
 
     // Tile number L (rows kinds) -> expert, row block inside the expert, column block.  Order inside an expert:
@@ -322,13 +325,14 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
             if (dynamic) {
                 // (agent-scope atomic: correct wherever the workgroups run; which tile a workgroup computes does not
                 // change the tile's value, so results stay bit-for-bit repeatable)
-                if (tid == 0) s_next = __hip_atomic_fetch_add(g.dyn_counters + xcd, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // (asking for the index one tile ahead, to hide the atomic's round trip, measured slower)
+                if (tid == 0) s_next = __hip_atomic_fetch_add(dyn_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __syncthreads();
                 const long item = s_next;
                 __syncthreads();                  // every wave has read it before the next fetch overwrites it
                 if (item >= n_dp) return false;
-                ord = (int)(item / per);
-                q = xcd * per + (int)(item - (long)ord * per);
+                if (per) { ord = (int)(item / per); q = xcd * per + (int)(item - (long)ord * per); }
+                else     { ord = (int)(item / tpe); q = (int)(item - (long)ord * tpe); }
             } else
             for (;;) {
                 const long round = dp_i / dp_stride, lanepos = dp_i - round * dp_stride;
