@@ -25,8 +25,8 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=16)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="C1", help="C0..C4 (C1 is the configuration the metric is quoted on)")
     ap.add_argument("--custom", default=None, metavar="N,d,h,E,k[,zipf_s]",
                     help="a bf16 layer of another shape (sweeps of experts / rows per expert); overrides --workload")
@@ -179,16 +179,18 @@ def run(a, torch, B, WORKLOADS, make_inputs):
     prof = B.moe_profile_read()
     B.moe_profile_enable(False)
 
-    flops_launch = 2.0 * w.M * w.d * w.h                     # one grouped product: 2 M d h
+    flops_product = 2.0 * w.M * w.d * w.h                    # one grouped product: 2 M d h
     kern = {n: {"launches_per_step": c / a.steps, "avg_us": 1e3 * t / c} for n, (c, t) in prof.items()}
     gemm = {n: v for n, v in prof.items() if n.startswith("ggemm_")}
+    products = {n: 2 if "+" in n else 1 for n in gemm}       # the bf16 backward runs two products per launch
     g_launches = sum(c for c, _ in gemm.values())
     g_ms = sum(t for _, t in gemm.values())
     avg_launch_ms = g_ms / g_launches
+    flops_launch = flops_product * sum(products[n] * c for n, (c, _) in gemm.items()) / g_launches   # mean per launch
     achieved = flops_launch / (avg_launch_ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if bf else PEAK_FP32_TFLOPS
     for n, (c, t) in gemm.items():
-        kern[n]["tflops"] = flops_launch / (t / c * 1e-3) / 1e12
+        kern[n]["tflops"] = products[n] * flops_product / (t / c * 1e-3) / 1e12
     # the data-movement kernels against the HBM roofline: algorithmic bytes per launch / mean duration
     eb = 2 if bf else 4
     Md, Nd = w.M * w.d * eb, w.N * w.d * eb
@@ -204,8 +206,10 @@ def run(a, torch, B, WORKLOADS, make_inputs):
         off, n = B.moe_workspace_region(desc, "clock")
         cyc, ticks = (int(v) for v in buf.workspace[off:off + n].view(torch.int64).cpu())
         clock_mhz = 100.0 * cyc / ticks if ticks > 0 else None
-    roofline = {"bound": "mfma" if bf else "alu", "kernel": "ggemm_sk_kernel (6 launches per step)" if bf
-                else "ggemm_f32_kernel (6 launches per step)",
+    roofline = {"bound": "mfma" if bf else "alu",
+                # (the bf16 backward puts dZ with dW2 and dXs with dW1 into one launch each where that pays)
+                "kernel": ("ggemm_sk_kernel / ggemm_pair_kernel" if bf else "ggemm_f32_kernel")
+                + " (%d launches of 6 products per step)" % round(g_launches / a.steps),
                 "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                 "traffic": MEASURED_HBM_BYTES_PER_GEMM_LAUNCH.get(w.name) if not a.custom else None,
                 "flops_per_launch": flops_launch, "avg_launch_us": avg_launch_ms * 1e3,

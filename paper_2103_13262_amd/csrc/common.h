@@ -155,6 +155,7 @@ struct GemmArgs {
     long long* clock_probe;    // [2]: shader cycles and 100 MHz ticks of workgroup 0 of the last launch
     const int32_t* skewed;     // 1: the experts' sizes are strongly skewed (decided by the plan step)
     int32_t* dyn_counters;     // [9]: next tile of every XCD's list and the number of workgroups that have finished; zero between launches
+    int on_demand;             // weight gradients: hand the tiles out from the counters whatever the sizes
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT
     long long* trace; // development builds only: per-workgroup phase times (8 words per workgroup) or NULL
@@ -163,6 +164,9 @@ void launch_segment_sums(const moe_desc_t& D, const WsLayout& L, const void* src
                          const int32_t* offsets, float* out, char* ws, hipStream_t st);
 void launch_ggemm_f32(const GemmArgs& a, hipStream_t st);
 void launch_ggemm_bf16_sk(const GemmArgs& a, hipStream_t st);
+// A rows kind (dZ or dXs) and a weight-gradient product that does not depend on it, in one launch.
+void launch_ggemm_pair_bf16_sk(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st);
+bool ggemm_pair_pays(const GemmArgs& rows);   // whether the pair launch is expected to beat two launches
 
 // ---- small device helpers ------------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }

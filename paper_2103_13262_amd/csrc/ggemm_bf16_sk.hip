@@ -102,7 +102,8 @@ struct Cfg {
     static constexpr int PATCH_BYTES = NW * 8 * PITCH * 4;    // 8 rows per wave
     static constexpr bool TABLE = KIND == kRowsNN_GeLU || KIND == kRowsNT_dGeLU;
     static constexpr int TABLE_BYTES = TABLE ? 2 * kActEntries * 4 : 0;
-    static constexpr int SMEM = RING + PATCH_BYTES + TABLE_BYTES;
+    static constexpr int NEXT_BYTES = KIND == kColsT ? 16 : 0;   // the tile index handed out on demand
+    static constexpr int SMEM = RING + PATCH_BYTES + TABLE_BYTES + NEXT_BYTES;
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile must split evenly over waves");
     static_assert(SMEM <= 160 * 1024, "LDS budget");
 };
@@ -171,7 +172,7 @@ struct Fin {              // what finishing an item needs once the streams have 
 };
 
 template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
-__global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, int ntm, int ntn)
+__device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int ntn)
 {
     using C = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
     constexpr int BM = C::BM, BN = C::BN, NT = C::NT, PITCH = C::PITCH;
@@ -205,8 +206,9 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     int tpe = 0, per = 0;            // weight gradients: tiles per expert, and per expert and XCD
     bool by_expert = false;          // weight gradients: every XCD works on whole experts (decided by the plan step)
     bool dynamic = false;            // weight gradients: tiles are taken from a per-XCD counter instead of in rounds
+    long n_static = 0;               // ... from this item of the list on; the items before it go in fixed rounds
     int32_t* dyn_ctr = nullptr;      // this workgroup's counter (one per XCD, or one for all when tiles are not split by XCD)
-    __shared__ int s_next;
+    int& s_next = *(int*)(smem + C::RING + C::PATCH_BYTES + C::TABLE_BYTES);   // (weight gradients only)
     if constexpr (KIND != kColsT) {
         const long T = (long)P[g.E] * ntn;
         const long base = T >> 3;
@@ -228,8 +230,14 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
         // workgroups that got the largest experts' tiles far behind.  Then the list (longest reductions first)
         // is handed out on demand from a counter.
         // (with a whole round inside one expert the fixed rounds are balanced already)
-        dynamic = !by_expert && (per == 0 || per < W) && *g.skewed != 0;
-        dyn_ctr = g.dyn_counters + (per ? xcd : 0);
+        // A launch that follows another product inside one kernel (on_demand) always does: its workgroups
+        // arrive at different times.
+        const bool skewed = *g.skewed != 0;
+        dynamic = g.on_demand || (!by_expert && (per == 0 || per < W) && skewed);
+        dyn_ctr = g.dyn_counters + (by_expert || per ? xcd : 0);
+        // An index from the counter costs a round trip to memory (about 2 us).  Sizes that are not skewed need the
+        // counter only to even out the workgroups' different arrival times: all but the last two rounds stay fixed.
+        if (dynamic && !skewed) n_static = max(0L, n_dp / dp_stride - 2) * dp_stride;
     }
 
     // Tile number L (rows kinds) -> expert, row block inside the expert, column block.  Order inside an expert:
@@ -326,13 +334,28 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
                 // (agent-scope atomic: correct wherever the workgroups run; which tile a workgroup computes does not
                 // change the tile's value, so results stay bit-for-bit repeatable)
                 // (asking for the index one tile ahead, to hide the atomic's round trip, measured slower)
-                if (tid == 0) s_next = __hip_atomic_fetch_add(dyn_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __syncthreads();
-                const long item = s_next;
-                __syncthreads();                  // every wave has read it before the next fetch overwrites it
-                if (item >= n_dp) return false;
-                if (per) { ord = (int)(item / per); q = xcd * per + (int)(item - (long)ord * per); }
-                else     { ord = (int)(item / tpe); q = (int)(item - (long)ord * tpe); }
+                for (;;) {
+                    long item;
+                    if (dp_i < n_static) {        // fixed rounds, alternating direction
+                        const long round = dp_i / dp_stride, lanepos = dp_i - round * dp_stride;
+                        item = round * dp_stride + ((round & 1) ? dp_stride - 1 - lanepos : lanepos);
+                        dp_i += dp_stride;
+                    } else {
+                        if (tid == 0) s_next = __hip_atomic_fetch_add(dyn_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __syncthreads();
+                        item = n_static + s_next;
+                        __syncthreads();          // every wave has read it before the next fetch overwrites it
+                    }
+                    if (item >= n_dp) return false;
+                    if (by_expert) {
+                        const int grp = (int)(item / tpe);
+                        ord = 8 * grp + ((grp & 1) ? 7 - xcd : xcd);
+                        q = (int)(item - (long)grp * tpe);
+                        if (ord >= g.E) continue; // (the last group of eight may be incomplete)
+                    } else if (per) { ord = (int)(item / per); q = xcd * per + (int)(item - (long)ord * per); }
+                    else            { ord = (int)(item / tpe); q = (int)(item - (long)ord * tpe); }
+                    break;
+                }
             } else
             for (;;) {
                 const long round = dp_i / dp_stride, lanepos = dp_i - round * dp_stride;
@@ -805,6 +828,24 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
 #endif
 }
 
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
+__global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, int ntm, int ntn)
+{
+    ggemm_sk_body<KIND, WM, WN, TM, TN, STAGES, BK>(g, ntm, ntn);
+}
+
+// Two products that do not depend on each other in one launch: a rows kind, then the weight gradients with their
+// tiles handed out on demand.  A workgroup that runs out of tiles of the first product goes on with the second
+// instead of idling until the launch ends, and one launch gap is saved.
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
+__global__ __launch_bounds__(512, 1) void ggemm_pair_kernel(GemmArgs g1, int ntn1, GemmArgs g2, int ntm2, int ntn2)
+{
+    static_assert(WM * WN * 64 == 512, "both products run on the same 8 waves");
+    ggemm_sk_body<KIND, WM, WN, TM, TN, STAGES, BK>(g1, 0, ntn1);
+    __syncthreads();   // the first product's last epilogue is done with the LDS before the second lays it out anew
+    ggemm_sk_body<kColsT, 2, 4, 4, 2, 4, 32>(g2, ntm2, ntn2);
+}
+
 // Persistent workgroups of one launch: one per compute unit, a multiple of the 8 XCDs, at most kMaxPersistentWgs
 // (the workspace holds one partial-sum buffer per workgroup).
 static int persistent_wgs()
@@ -895,6 +936,54 @@ template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
     else launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st);
 }
 }  // namespace sk
+
+namespace sk {
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
+void launch_pair_cfg(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
+{
+    using C1 = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
+    using C2 = Cfg<kColsT, 2, 4, 4, 2, 4, 32>;
+    constexpr int SMEM = C1::SMEM > C2::SMEM ? C1::SMEM : C2::SMEM;
+    auto kern = ggemm_pair_kernel<KIND, WM, WN, TM, TN, STAGES, BK>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess) return;
+        attr_set = true;
+    }
+    const int wgs = persistent_wgs();
+    if (wgs < 8) { set_error("grouped GEMM: no device with at least 8 compute units"); return; }
+    GemmArgs r = rows, c = cols;
+    r.trace = nullptr;  c.trace = nullptr;
+    c.on_demand = 1;
+    const int ntn1 = (r.Nout + C1::BN - 1) / C1::BN;
+    const int ntn2 = (c.Nout + C2::BN - 1) / C2::BN, ntm2 = (c.K + C2::BM - 1) / C2::BM;
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(512), SMEM, st, r, ntn1, c, ntm2, ntn2);
+}
+
+template <int KIND> void launch_pair_kind(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
+{
+    if (rows.M < 96L * rows.E) launch_pair_cfg<KIND, 1, 8, 2, 1, 3, 64>(rows, cols, st);   // as in launch_kind
+    else launch_pair_cfg<KIND, 2, 4, 4, 2, 2, 64>(rows, cols, st);
+}
+}  // namespace sk
+
+// With few tiles per workgroup the ragged end of a rows-kind launch (a quarter to half a tile per workgroup) and the
+// launch gap are worth more than the counter's round trips; measured, the pair wins up to about 8 tiles per
+// workgroup (C1: -3 % per step, C2: -1.4 %) and loses 0.5 % at 34 (C4).
+bool ggemm_pair_pays(const GemmArgs& rows)
+{
+    const int wgs = sk::persistent_wgs();
+    if (wgs < 8) return false;
+    const long row_tiles = rows.M / 256 + rows.E / 2, col_tiles = (rows.Nout + 255) / 256;
+    return row_tiles * col_tiles <= 8L * wgs;
+}
+
+void launch_ggemm_pair_bf16_sk(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
+{
+    using namespace sk;
+    if (rows.kind == kRowsNT_dGeLU) launch_pair_kind<kRowsNT_dGeLU>(rows, cols, st);
+    else launch_pair_kind<kRowsNT>(rows, cols, st);
+}
 
 void launch_ggemm_bf16_sk(const GemmArgs& a, hipStream_t st)
 {

@@ -34,10 +34,11 @@ moe_status_t check_launch(const char* what)
 }
 
 // ---- optional per-kernel timing (diagnostics) --------------------------------------------------
-enum Slot { S_GATE, S_PLAN, S_SCATTER, S_FC1, S_FC2, S_COMBINE, S_DCOMBINE, S_DH, S_DW2, S_DXS, S_DW1, S_GATEBWD, S_COUNT };
+enum Slot { S_GATE, S_PLAN, S_SCATTER, S_FC1, S_FC2, S_COMBINE, S_DCOMBINE, S_DH, S_DW2, S_DXS, S_DW1, S_GATEBWD,
+            S_DH_DW2, S_DXS_DW1, S_COUNT };
 static const char* const kSlotNames[S_COUNT] = {"gate_topk", "plan", "scatter", "ggemm_fc1_gelu", "ggemm_fc2",
                                                 "combine", "dcombine", "ggemm_dh_dgelu", "ggemm_dw2", "ggemm_dxs",
-                                                "ggemm_dw1", "gate_bwd"};
+                                                "ggemm_dw1", "gate_bwd", "ggemm_dh_dgelu+dw2", "ggemm_dxs+dw1"};
 struct TimedRecord { int slot; hipEvent_t a, b; };
 static std::mutex g_prof_mu;
 static bool g_prof_on = false;
@@ -340,28 +341,41 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     a.out_f32 = D.grad_dtype == MOE_F32;
     a.accumulate = D.accumulate;
 
-    if (D.N > 0) {
-        a.kind = kRowsNT_dGeLU;  // dZ = (dYs W2[e]^T) .* GeLU'(Z)
-        a.A = ws + L.dYs; a.B = W2; a.C = ws + L.dZ; a.Zin = ws + L.Z; a.K = D.d; a.Nout = D.h;
-        { ScopedTimer tm(S_DH, st); run_gemm(D, a, st); }
-        if ((s = check_launch("expert layer 2 data gradient")) != MOE_OK) return s;
+    GemmArgs dh = a, dw2 = a, dxs = a, dw1 = a;
+    dh.kind = kRowsNT_dGeLU;     // dZ = (dYs W2[e]^T) .* GeLU'(Z)
+    dh.A = ws + L.dYs; dh.B = W2; dh.C = ws + L.dZ; dh.Zin = ws + L.Z; dh.K = D.d; dh.Nout = D.h;
+    dw2.kind = kColsT;           // dW2[e] = H[seg]^T dYs[seg]
+    dw2.A = ws + L.H; dw2.B = ws + L.dYs; dw2.C = dW2; dw2.K = D.h; dw2.Nout = D.d;
+    dxs.kind = kRowsNT;          // dXs = dZ W1[e]^T
+    dxs.A = ws + L.dZ; dxs.B = W1; dxs.C = ws + L.dXs; dxs.K = D.h; dxs.Nout = D.d;
+    dw1.kind = kColsT;           // dW1[e] = Xs[seg]^T dZ[seg]
+    dw1.A = ws + L.Xs; dw1.B = ws + L.dZ; dw1.C = dW1; dw1.K = D.d; dw1.Nout = D.h;
+    // dZ and dW2 need only dYs, and dXs and dW1 only dZ: where it pays, each pair is one launch in which a workgroup
+    // that has finished its share of the first product goes on with tiles of the second.
+    const bool can_pair = D.dtype == MOE_BF16 && D.N > 0;
+    if (can_pair && ggemm_pair_pays(dh)) {
+        { ScopedTimer tm(S_DH_DW2, st); launch_ggemm_pair_bf16_sk(dh, dw2, st); }
+        if ((s = check_launch("expert layer 2 gradients")) != MOE_OK) return s;
+    } else {
+        if (D.N > 0) {
+            { ScopedTimer tm(S_DH, st); run_gemm(D, dh, st); }
+            if ((s = check_launch("expert layer 2 data gradient")) != MOE_OK) return s;
+        }
+        // The weight-gradient launches also run for N == 0: they write zeros (or leave the buffers when accumulating).
+        { ScopedTimer tm(S_DW2, st); run_gemm(D, dw2, st); }
+        if ((s = check_launch("expert layer 2 weight gradient")) != MOE_OK) return s;
     }
-    // The weight-gradient launches also run for N == 0: they write zeros (or leave the buffers when accumulating).
-    a.kind = kColsT;             // dW2[e] = H[seg]^T dYs[seg]
-    a.A = ws + L.H; a.B = ws + L.dYs; a.C = dW2; a.Zin = nullptr; a.K = D.h; a.Nout = D.d;
-    { ScopedTimer tm(S_DW2, st); run_gemm(D, a, st); }
-    if ((s = check_launch("expert layer 2 weight gradient")) != MOE_OK) return s;
-
-    if (D.N > 0) {
-        a.kind = kRowsNT;        // dXs = dZ W1[e]^T
-        a.A = ws + L.dZ; a.B = W1; a.C = ws + L.dXs; a.K = D.h; a.Nout = D.d;
-        { ScopedTimer tm(S_DXS, st); run_gemm(D, a, st); }
-        if ((s = check_launch("expert layer 1 data gradient")) != MOE_OK) return s;
+    if (can_pair && ggemm_pair_pays(dxs)) {
+        { ScopedTimer tm(S_DXS_DW1, st); launch_ggemm_pair_bf16_sk(dxs, dw1, st); }
+        if ((s = check_launch("expert layer 1 gradients")) != MOE_OK) return s;
+    } else {
+        if (D.N > 0) {
+            { ScopedTimer tm(S_DXS, st); run_gemm(D, dxs, st); }
+            if ((s = check_launch("expert layer 1 data gradient")) != MOE_OK) return s;
+        }
+        { ScopedTimer tm(S_DW1, st); run_gemm(D, dw1, st); }
+        if ((s = check_launch("expert layer 1 weight gradient")) != MOE_OK) return s;
     }
-    a.kind = kColsT;             // dW1[e] = Xs[seg]^T dZ[seg]
-    a.A = ws + L.Xs; a.B = ws + L.dZ; a.C = dW1; a.K = D.d; a.Nout = D.h;
-    { ScopedTimer tm(S_DW1, st); run_gemm(D, a, st); }
-    if ((s = check_launch("expert layer 1 weight gradient")) != MOE_OK) return s;
 
     {
         ScopedTimer tm(S_GATEBWD, st);

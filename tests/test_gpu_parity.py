@@ -49,6 +49,8 @@ CASES = [
     # pieces of their reduction; in the first case a workgroup ends one tile and begins the next
     Workload("split_reduction_bf16", 360, 64, 384, 12, 2, "bf16", 0.0, 22),
     Workload("split_reduction_deep_bf16", 200, 64, 1024, 3, 2, "bf16", 0.0, 23),
+    # one expert takes most rows: the weight-gradient tiles (8 per expert: one per XCD) are handed out on demand
+    Workload("dw_on_demand_bf16", 230, 512, 1024, 8, 2, "bf16", 2.0, 37),
 ]
 
 
@@ -201,14 +203,17 @@ def test_empty_batch_and_repeatability():
     assert not np.any(to_numpy64(run.dW1)) and not np.any(to_numpy64(run.dW2)) and not np.any(to_numpy64(run.dWg))
 
     # two runs of the same problem give identical bits (fixed reduction orders, no float atomics)
-    w = Workload("repeat", 900, 128, 192, 7, 2, "bf16", 1.0, 42)
-    inp = make_inputs(w)
-    a = GpuRun(w, inp).run()
-    b = GpuRun(w, inp).run()
-    for name in ("Y", "dX", "dW1", "dW2", "dWg", "dbg"):
-        ta, tb = getattr(a, name), getattr(b, name)
-        assert torch.equal(ta.view(torch.int16 if ta.dtype == torch.bfloat16 else torch.int32),
-                           tb.view(torch.int16 if tb.dtype == torch.bfloat16 else torch.int32)), name
+    # (the second shape hands its weight-gradient tiles out on demand: which workgroup computes a tile varies
+    # from run to run, the tile's value must not)
+    for w in (Workload("repeat", 900, 128, 192, 7, 2, "bf16", 1.0, 42),
+              Workload("repeat_on_demand", 3000, 512, 1024, 8, 2, "bf16", 2.0, 43)):
+        inp = make_inputs(w)
+        a = GpuRun(w, inp).run()
+        b = GpuRun(w, inp).run()
+        for name in ("Y", "dX", "dW1", "dW2", "dWg", "dbg"):
+            ta, tb = getattr(a, name), getattr(b, name)
+            assert torch.equal(ta.view(torch.int16 if ta.dtype == torch.bfloat16 else torch.int32),
+                               tb.view(torch.int16 if tb.dtype == torch.bfloat16 else torch.int32)), (w.name, name)
 
 
 def test_accumulate_adds_to_existing_gradients():
