@@ -63,11 +63,11 @@ def cpu_baseline(w, inputs, n_tokens):
                       f"weight gradients, {dt:.1f} s"}
 
 
-# HBM bytes per grouped-GEMM launch (mean of the six launches of a step), from two rocprofv3 --pmc runs of this
+# HBM bytes per grouped-GEMM launch (mean of the four launches of a step, which hold six products), from two rocprofv3 --pmc runs of this
 # file (FETCH_SIZE, then WRITE_SIZE), each divided by what the same counter reads for a plain 1 GiB copy
 # (0.500 and 1.000 of the true KiB); profiles/C1_hbm_traffic_pmc.md holds the commands and per-kernel figures.
 # Counters cannot be read from inside a run, so this is the stored measurement, not a live one.
-MEASURED_HBM_BYTES_PER_GEMM_LAUNCH = {"C1": 386.7e6}
+MEASURED_HBM_BYTES_PER_GEMM_LAUNCH = {"C1": 618.2e6}
 
 
 def main():
