@@ -222,7 +222,8 @@ moe_status_t moe_workspace_region(const moe_desc_t *desc, const char *name, size
  *     (negative status on a HIP error).  `name` points to static storage.
  */
 typedef struct {
-    const char *name; /* e.g. "ggemm_fc1_gelu", "scatter"                                        */
+    const char *name; /* e.g. "ggemm_fc1_gelu", "scatter"; "ggemm_dxs+dw1" is one launch that   */
+                      /* holds two grouped products                                             */
     int32_t launches; /* launches recorded since the last read                                  */
     double total_ms;  /* summed device time of those launches                                   */
 } moe_kernel_time_t;

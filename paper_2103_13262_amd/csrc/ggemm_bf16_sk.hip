@@ -11,6 +11,9 @@
 //     order (a fixed order: results do not depend on timing) and the workgroup whose range holds the tile's
 //     last block writes the tile.  Every workgroup handles the piece at the end of its range first, and a
 //     workgroup waits only for the one numbered just below it, so the waits cannot form a cycle.
+// The weight gradients (whole tiles only: their reduction runs over an expert's rows) take their tiles in fixed
+// rounds too, or - when the experts' sizes are strongly skewed, or when they follow another product inside one
+// launch (ggemm_pair_kernel) - from counters in memory, on demand.
 // Operands travel from global memory straight into an LDS ring (global_load_lds_dwordx4), the first blocks
 // of the next work item are requested before the epilogue of the current one, and the epilogue runs through
 // a small LDS patch of its own so that it does not disturb the ring.
