@@ -14,6 +14,16 @@ constexpr int kPlanChunk = 1024;  // assignments ranked by one workgroup of the 
 constexpr int kNumTileHeights = 4;  // row-tile prefix tables are kept for 32, 64, 128, 256 rows
 constexpr int kMaxPersistentWgs = 256;               // persistent grouped-GEMM workgroups (one per compute unit)
 constexpr size_t kPartialBytesPerWg = 256 * 256 * 4;  // one fp32 output tile of partial sums per workgroup
+// Size classes of an expert's rows for the bf16 row products: whole blocks of kClsBigRows rows, computed in
+// 256 x 256 tiles, and a last piece of at most kClsSmallRows rows, computed in 128 x 512 tiles (half as many tiles
+// for it).  A last piece longer than that counts as one more big block.  Tables, each [E+1]:
+constexpr int kClsBigRows = 256, kClsSmallRows = 128;
+enum { kClsCountsBig = 0,    // rows of the expert that the big tiles cover
+       kClsCountsSmall = 1,  // rows of its last piece (0: none)
+       kClsOffsetsSmall = 2, // first row of the last piece
+       kClsPBig = 3,         // prefix of the number of big row blocks ([E] = total)
+       kClsPSmall = 4,       // prefix of the number of last pieces ([E] = total)
+       kClsTables = 5 };
 __host__ __device__ constexpr int tile_height(int q) { return 32 << q; }
 __host__ __device__ constexpr int tile_height_index(int bm) { return bm == 32 ? 0 : bm == 64 ? 1 : bm == 128 ? 2 : 3; }
 
@@ -23,6 +33,7 @@ struct WsLayout {
     size_t dl;        // [M]  float: gradient of the selected logits, by assignment
     size_t tileP;     // [4][E+1] int32: prefix of ceil(counts/BM) for BM = 32,64,128,256
     size_t order;     // [E] int32: experts by descending count (ties: lower id first)
+    size_t cls;       // [5][E+1] int32: the experts' rows in two size classes (see kCls* below)
     size_t hist;      // [nb][E] int32: per plan-chunk histogram, then exclusive base inside the expert
     size_t dwg_part;  // [pieces][d] float: partial sums of dWg over pieces of 64 rows
     size_t dbg_part;  // [pieces] float
@@ -68,6 +79,7 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.dl = take(M * sizeof(float));
     L.tileP = take((size_t)kNumTileHeights * (D.E + 1) * sizeof(int32_t));
     L.order = take((size_t)D.E * sizeof(int32_t));
+    L.cls = take((size_t)kClsTables * (D.E + 1) * sizeof(int32_t));
     L.nb = (int)((M + kPlanChunk - 1) / kPlanChunk);
     L.hist = take((size_t)(L.nb > 0 ? L.nb : 1) * D.E * sizeof(int32_t));
     L.dwg_pieces = (long)(M / 64) + D.E;
@@ -147,6 +159,7 @@ struct GemmArgs {
     const int32_t* offsets;
     const int32_t* tileP;  // [4][E+1]
     const int32_t* order;  // [E]
+    const int32_t* cls;    // [kClsTables][E+1] size-class tables of the plan step, or NULL (bf16 row products only)
     const void* zeros;     // 1 KB of zeros
     void* sk_part;         // partial-sum tiles, one per persistent workgroup
     int32_t* sk_flags;     // one flag per persistent workgroup, all zero between launches

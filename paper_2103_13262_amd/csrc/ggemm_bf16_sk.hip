@@ -174,10 +174,17 @@ struct Fin {              // what finishing an item needs once the streams have 
     int Mt, Nt, owner;
 };
 
-template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
-__device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int ntn)
+// CLS: 0 = all rows of every expert (tables counts / offsets / tileP); 1 = the rows in whole blocks of
+// kClsBigRows, 2 = the experts' last pieces (the plan step's size-class tables; rows kinds only).
+// Of every XCD's workgroups, those numbered wj_base .. wj_base + wj_count - 1 take part (wj_count <= 0: all); the
+// others return at once.
+template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK, int CLS = 0>
+__device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int ntn, int wj_base = 0, int wj_count = 0)
 {
     using C = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
+    static_assert(CLS == 0 || (KIND != kColsT && C::BM == (CLS == 1 ? kClsBigRows : kClsSmallRows)), "size class and tile height");
+    const int32_t* const counts_ = CLS == 0 ? g.counts : g.cls + (CLS == 1 ? kClsCountsBig : kClsCountsSmall) * (g.E + 1);
+    const int32_t* const offsets_ = CLS == 2 ? g.cls + kClsOffsetsSmall * (g.E + 1) : g.offsets;
     constexpr int BM = C::BM, BN = C::BN, NT = C::NT, PITCH = C::PITCH;
     extern __shared__ __align__(1024) char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -197,8 +204,10 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
     const long long probe_cycles0 = clock64(), probe_ticks0 = wall_clock64();
 
     // ---------------- schedule of this workgroup ----------------
-    const int xcd = blockIdx.x & 7, wj = blockIdx.x >> 3, W = gridDim.x >> 3;
-    const int32_t* P = g.tileP + tile_height_index(BM) * (g.E + 1);
+    const int xcd = blockIdx.x & 7, wj = (int)(blockIdx.x >> 3) - wj_base, W = wj_count > 0 ? wj_count : (int)(gridDim.x >> 3);
+    if (wj < 0 || wj >= W) return;
+    const int32_t* P = CLS == 0 ? g.tileP + tile_height_index(BM) * (g.E + 1)
+                                : g.cls + (CLS == 1 ? kClsPBig : kClsPSmall) * (g.E + 1);
     long start = 0, n_dp = 0;        // rows kinds: first tile of this XCD's share; number of whole-tile items
     int rem = 0, Wp = 0;             // left-over tiles of this XCD; workgroups taking part in their reduction split
     int row_f = 1;                   // left-over tiles cut into this many row slices instead
@@ -274,7 +283,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         int e, mt, nt;
         locate(L, e, mt, nt);
         const int rows_per = BM / f, row_off = slice * rows_per;
-        const long r0 = (long)g.offsets[e] + (long)mt * BM + row_off;
+        const long r0 = (long)offsets_[e] + (long)mt * BM + row_off;
         const int n0 = nt * BN;
         it.A = (const u16*)g.A + r0 * g.K;  it.lda = g.K;
         const u16* Be = (const u16*)g.B + (size_t)e * g.K * g.Nout;
@@ -282,7 +291,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         else                      { it.B = Be + (size_t)n0 * g.K; it.ldb = g.K; }
         it.c_off = (size_t)r0 * g.Nout + n0;
         it.b_off = (size_t)e * g.Nout + n0;
-        it.Mt = min(rows_per, g.counts[e] - mt * BM - row_off);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.K;
+        it.Mt = min(rows_per, counts_[e] - mt * BM - row_off);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.K;
     };
     if constexpr (KIND != kColsT) {
         if (rem) {
@@ -776,7 +785,8 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         // built while the first blocks are on their way; visible to all waves after the first barrier, long
         // before the first epilogue (every item of these kinds has at least one block)
         float* w = (float*)(smem + C::RING + C::PATCH_BYTES);
-        for (int i = tid; i < 2 * kActEntries; i += NT) w[i] = act_entry<KIND>(i);
+        if (have)
+            for (int i = tid; i < 2 * kActEntries; i += NT) w[i] = act_entry<KIND>(i);
     }
     TRACE_PHASE(0);
     while (have) {
@@ -837,15 +847,49 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
     ggemm_sk_body<KIND, WM, WN, TM, TN, STAGES, BK>(g, ntm, ntn);
 }
 
+// The rows of every expert in two size classes, one after the other in one launch: whole blocks of 256 rows in
+// 256 x 256 tiles, then the experts' last pieces (at most 128 rows) in 128 x 512 tiles.  The main loop's pace is set by
+// the arrival of the operand blocks, not by what a tile holds, so a last piece costs half as much in tiles twice as wide.
+template <int KIND, int STAGES, int BK>
+__device__ __forceinline__ void ggemm_classes(const GemmArgs& g, int ntn_big, int ntn_small)
+{
+    const int W = gridDim.x >> 3;
+    const long Tb = (long)g.cls[kClsPBig * (g.E + 1) + g.E] * ntn_big, Ts = (long)g.cls[kClsPSmall * (g.E + 1) + g.E] * ntn_small;
+    if (Ts == 0) { ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big); return; }
+    if (g.K >= 2 * kMinSplitDepth && W >= 2 && Tb < 8L * W) {
+        // Deep reductions with less than a round of tiles are cut into equal pieces over the workgroups, so a second
+        // phase for the last pieces would leave most workgroups idle: the two classes run side by side instead, on
+        // shares of every XCD's workgroups in proportion to their operand bytes (a 128 x 512 tile moves 5/4 of what a
+        // 256 x 256 tile moves).  (With whole rounds of tiles the shares would have to match the classes' times more
+        // closely than such an estimate can: measured 7 % slower on a large problem.)
+        const long cs = Ts * 5, cb = Tb * 4;
+        int ws = Tb == 0 ? W : (int)((W * cs + (cs + cb) / 2) / (cs + cb));
+        ws = Tb == 0 ? W : ws < 1 ? 1 : ws > W - 1 ? W - 1 : ws;
+        ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big, 0, W - ws);
+        ggemm_sk_body<KIND, 1, 8, 4, 2, 3, 32, 2>(g, 0, ntn_small, W - ws, ws);   // (a workgroup runs one of the two)
+        return;
+    }
+    ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big);
+    __syncthreads();   // the first class's last epilogue is done with the LDS before the second lays it out anew
+    ggemm_sk_body<KIND, 1, 8, 4, 2, 3, 32, 2>(g, 0, ntn_small);
+}
+
+template <int KIND, int STAGES, int BK>
+__global__ __launch_bounds__(512, 1) void ggemm_cls_kernel(GemmArgs g, int ntn_big, int ntn_small)
+{
+    ggemm_classes<KIND, STAGES, BK>(g, ntn_big, ntn_small);
+}
+
 // Two products that do not depend on each other in one launch: a rows kind, then the weight gradients with their
 // tiles handed out on demand.  A workgroup that runs out of tiles of the first product goes on with the second
-// instead of idling until the launch ends, and one launch gap is saved.
-template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
-__global__ __launch_bounds__(512, 1) void ggemm_pair_kernel(GemmArgs g1, int ntn1, GemmArgs g2, int ntm2, int ntn2)
+// instead of idling until the launch ends, and one launch gap is saved.  CLASSES: the rows kind in size classes
+// (as ggemm_cls_kernel), else in 64 x 256 tiles (many small experts).
+template <int KIND, bool CLASSES>
+__global__ __launch_bounds__(512, 1) void ggemm_pair_kernel(GemmArgs g1, int ntn1, int ntn1_small, GemmArgs g2, int ntm2, int ntn2)
 {
-    static_assert(WM * WN * 64 == 512, "both products run on the same 8 waves");
-    ggemm_sk_body<KIND, WM, WN, TM, TN, STAGES, BK>(g1, 0, ntn1);
-    __syncthreads();   // the first product's last epilogue is done with the LDS before the second lays it out anew
+    if constexpr (CLASSES) ggemm_classes<KIND, 2, 64>(g1, ntn1, ntn1_small);
+    else ggemm_sk_body<KIND, 1, 8, 2, 1, 3, 64>(g1, 0, ntn1);
+    __syncthreads();
     ggemm_sk_body<kColsT, 2, 4, 4, 2, 4, 32>(g2, ntm2, ntn2);
 }
 
@@ -921,6 +965,27 @@ void launch_cfg(const GemmArgs& a, hipStream_t st)
 #endif
 }
 
+template <int KIND, int STAGES, int BK>
+void launch_cls(const GemmArgs& a, hipStream_t st)
+{
+    using C1 = Cfg<KIND, 2, 4, 4, 2, STAGES, BK>;
+    using C2 = Cfg<KIND, 1, 8, 4, 2, 3, 32>;
+    static_assert((size_t)C2::BM * C2::BN * 4 <= kPartialBytesPerWg, "partial-sum buffer");
+    constexpr int SMEM = C1::SMEM > C2::SMEM ? C1::SMEM : C2::SMEM;
+    auto kern = ggemm_cls_kernel<KIND, STAGES, BK>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess) return;
+        attr_set = true;
+    }
+    const int wgs = persistent_wgs();
+    if (wgs < 8) { set_error("grouped GEMM: no device with at least 8 compute units"); return; }
+    GemmArgs b = a;
+    b.trace = nullptr;
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(512), SMEM, st, b, (a.Nout + C1::BN - 1) / C1::BN,
+                       (a.Nout + C2::BN - 1) / C2::BN);
+}
+
 template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
 {
     // 256 x 256 tile, 8 waves of 128 x 64, and a 128 KB ring: two slots of 64-deep blocks, or four slots of 32-deep
@@ -932,22 +997,27 @@ template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
     // Many small experts (fewer than 96 rows on average): 64 x 256 tiles, 8 waves of 64 x 32, 3 ring slots, so that a
     // tile is not mostly rows that do not exist.  (The weight gradients keep the large tile: their tile spans the
     // weight matrix, not the expert's rows.)
+    // Otherwise the rows kinds run in two size classes (launch_cls): an expert's last few rows in 128 x 512 tiles.
     if constexpr (KIND != kColsT) {
         if (a.M < 96L * a.E) { launch_cfg<KIND, 1, 8, 2, 1, 3, 64>(a, st); return; }
+        if (!a.cls) { set_error("grouped GEMM: the plan step's size-class tables are missing"); return; }
+        if constexpr (KIND == kRowsNN) launch_cls<KIND, 4, 32>(a, st);
+        else launch_cls<KIND, 2, 64>(a, st);
+    } else {
+        launch_cfg<KIND, 2, 4, 4, 2, 4, 32>(a, st);
     }
-    if constexpr (KIND == kColsT || KIND == kRowsNN) launch_cfg<KIND, 2, 4, 4, 2, 4, 32>(a, st);
-    else launch_cfg<KIND, 2, 4, 4, 2, 2, 64>(a, st);
 }
 }  // namespace sk
 
 namespace sk {
-template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
+template <int KIND, bool CLASSES>
 void launch_pair_cfg(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
 {
-    using C1 = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
+    using C1 = std::conditional_t<CLASSES, Cfg<KIND, 2, 4, 4, 2, 2, 64>, Cfg<KIND, 1, 8, 2, 1, 3, 64>>;
+    using C1s = Cfg<KIND, 1, 8, 4, 2, 3, 32>;
     using C2 = Cfg<kColsT, 2, 4, 4, 2, 4, 32>;
-    constexpr int SMEM = C1::SMEM > C2::SMEM ? C1::SMEM : C2::SMEM;
-    auto kern = ggemm_pair_kernel<KIND, WM, WN, TM, TN, STAGES, BK>;
+    constexpr int SMEM = std::max({C1::SMEM, CLASSES ? C1s::SMEM : 0, C2::SMEM});
+    auto kern = ggemm_pair_kernel<KIND, CLASSES>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess) return;
@@ -958,15 +1028,15 @@ void launch_pair_cfg(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
     GemmArgs r = rows, c = cols;
     r.trace = nullptr;  c.trace = nullptr;
     c.on_demand = 1;
-    const int ntn1 = (r.Nout + C1::BN - 1) / C1::BN;
+    const int ntn1 = (r.Nout + C1::BN - 1) / C1::BN, ntn1s = (r.Nout + C1s::BN - 1) / C1s::BN;
     const int ntn2 = (c.Nout + C2::BN - 1) / C2::BN, ntm2 = (c.K + C2::BM - 1) / C2::BM;
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(512), SMEM, st, r, ntn1, c, ntm2, ntn2);
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(512), SMEM, st, r, ntn1, ntn1s, c, ntm2, ntn2);
 }
 
 template <int KIND> void launch_pair_kind(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
 {
-    if (rows.M < 96L * rows.E) launch_pair_cfg<KIND, 1, 8, 2, 1, 3, 64>(rows, cols, st);   // as in launch_kind
-    else launch_pair_cfg<KIND, 2, 4, 4, 2, 2, 64>(rows, cols, st);
+    if (rows.M < 96L * rows.E) launch_pair_cfg<KIND, false>(rows, cols, st);   // as in launch_kind
+    else launch_pair_cfg<KIND, true>(rows, cols, st);
 }
 }  // namespace sk
 

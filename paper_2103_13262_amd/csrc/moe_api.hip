@@ -267,6 +267,7 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     a.offsets = plan->offsets;
     a.tileP = (const int32_t*)(ws + L.tileP);
     a.order = (const int32_t*)(ws + L.order);
+    a.cls = (const int32_t*)(ws + L.cls);
     a.zeros = ws + L.zeros;
     a.sk_part = ws + L.sk_part;
     a.sk_flags = (int32_t*)(ws + L.sk_flags);
@@ -330,6 +331,7 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     a.offsets = plan->offsets;
     a.tileP = (const int32_t*)(ws + L.tileP);
     a.order = (const int32_t*)(ws + L.order);
+    a.cls = (const int32_t*)(ws + L.cls);
     a.zeros = ws + L.zeros;
     a.sk_part = ws + L.sk_part;
     a.sk_flags = (int32_t*)(ws + L.sk_flags);

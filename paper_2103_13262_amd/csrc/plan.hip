@@ -60,7 +60,8 @@ constexpr int kFusedHistInts = 8192;   // chunk histograms that plan_scan builds
 __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ idx, int32_t* __restrict__ hist, int nb,
                                                   int E, long M, int32_t* __restrict__ counts,
                                                   int32_t* __restrict__ offsets, int32_t* __restrict__ tileP,
-                                                  int32_t* __restrict__ order, int32_t* __restrict__ zeros)
+                                                  int32_t* __restrict__ order, int32_t* __restrict__ cls,
+                                                  int32_t* __restrict__ zeros)
 {
     // page read in place of masked rows, and the flags of the persistent matrix-product kernels behind it
     if (threadIdx.x < (int)(kZeroedBytes / 4)) zeros[threadIdx.x] = 0;
@@ -121,6 +122,21 @@ __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ id
         const int p = block_excl_scan_1024(nt, s_wave, &total);
         if (e < E) tileP[q * (E + 1) + e] = p;
         if (e == 0) tileP[q * (E + 1) + E] = total;
+    }
+    {   // the two size classes of every expert's rows
+        int nbig = cnt / kClsBigRows, last = cnt - nbig * kClsBigRows;
+        if (last > kClsSmallRows) { ++nbig; last = 0; }
+        if (e < E) {
+            cls[kClsCountsBig * (E + 1) + e] = min(cnt, nbig * kClsBigRows);
+            cls[kClsCountsSmall * (E + 1) + e] = last;
+            cls[kClsOffsetsSmall * (E + 1) + e] = off + nbig * kClsBigRows;
+        }
+        int p = block_excl_scan_1024(e < E ? nbig : 0, s_wave, &total);
+        if (e < E) cls[kClsPBig * (E + 1) + e] = p;
+        if (e == 0) cls[kClsPBig * (E + 1) + E] = total;
+        p = block_excl_scan_1024(e < E && last > 0 ? 1 : 0, s_wave, &total);
+        if (e < E) cls[kClsPSmall * (E + 1) + e] = p;
+        if (e == 0) cls[kClsPSmall * (E + 1) + E] = total;
     }
     __syncthreads();
     int rank = 0;                         // experts by descending count, ties by ascending id
@@ -217,7 +233,7 @@ void launch_plan(const moe_desc_t& D, const WsLayout& L, const int32_t* topk_idx
     const bool fused = L.nb > 0 && (long)L.nb * D.E <= kFusedHistInts;
     if (L.nb > 0 && !fused) hipLaunchKernelGGL(plan_hist, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, hist);
     hipLaunchKernelGGL(plan_scan, dim3(1), dim3(1024), 0, st, fused ? topk_idx : (const int32_t*)nullptr, hist, L.nb, D.E,
-                       M, counts, offsets, tileP, order, (int32_t*)(ws + L.zeros));
+                       M, counts, offsets, tileP, order, (int32_t*)(ws + L.cls), (int32_t*)(ws + L.zeros));
     if (L.nb > 0)
         hipLaunchKernelGGL(plan_rank, dim3(L.nb), dim3(256), 0, st, topk_idx, M, D.E, nbits, (const int32_t*)hist,
                            (const int32_t*)offsets, pos, perm);
