@@ -11,6 +11,8 @@
 //     order (a fixed order: results do not depend on timing) and the workgroup whose range holds the tile's
 //     last block writes the tile.  Every workgroup handles the piece at the end of its range first, and a
 //     workgroup waits only for the one numbered just below it, so the waits cannot form a cycle.
+// The rows kinds compute an expert's whole blocks of 256 rows in 256 x 256 tiles and its last piece (at most 128 rows)
+// in 128 x 512 tiles, from the plan step's size-class tables (ggemm_cls_kernel); many small experts: 64 x 256 tiles.
 // The weight gradients (whole tiles only: their reduction runs over an expert's rows) take their tiles in fixed
 // rounds too, or - when the experts' sizes are strongly skewed, or when they follow another product inside one
 // launch (ggemm_pair_kernel) - from counters in memory, on demand.
