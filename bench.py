@@ -208,7 +208,7 @@ def run(a, torch, B, WORKLOADS, make_inputs):
         clock_mhz = 100.0 * cyc / ticks if ticks > 0 else None
     roofline = {"bound": "mfma" if bf else "alu",
                 # (the bf16 backward puts dZ with dW2 and dXs with dW1 into one launch each where that pays)
-                "kernel": ("ggemm_sk_kernel / ggemm_pair_kernel" if bf else "ggemm_f32_kernel")
+                "kernel": ("ggemm_cls_kernel / ggemm_pair_kernel / ggemm_sk_kernel" if bf else "ggemm_f32_kernel")
                 + " (%d launches of 6 products per step)" % round(g_launches / a.steps),
                 "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                 "traffic": MEASURED_HBM_BYTES_PER_GEMM_LAUNCH.get(w.name) if not a.custom else None,
