@@ -63,11 +63,12 @@ def max_err_over_max(got, ref):
     return diff / top
 
 
-def _full_check(w, grad_dtype=None):
+def _full_check(w, grad_dtype=None, inputs=None):
     import oracle as orc
 
     print(f"[case] {w}", flush=True)
-    inputs = make_inputs(w)
+    if inputs is None:
+        inputs = make_inputs(w)
     run = GpuRun(w, inputs, grad_dtype=grad_dtype).run()
     ref_plan = check_plan_exact(run, inputs)
     ref = orc.layer(oracle_problem(w, inputs), want_internals=True)
@@ -214,6 +215,40 @@ def test_empty_batch_and_repeatability():
             ta, tb = getattr(a, name), getattr(b, name)
             assert torch.equal(ta.view(torch.int16 if ta.dtype == torch.bfloat16 else torch.int32),
                                tb.view(torch.int16 if tb.dtype == torch.bfloat16 else torch.int32)), (w.name, name)
+
+
+def _routed_inputs(w, counts):
+    """The workload's inputs with the gate replaced by one that sends exactly counts[e] tokens to expert e (top-1):
+    feature e of a token is 1 for its expert and 0 for the others, and the gate matrix copies the first E features.
+    (A larger marker would give one row of dW1 sums of equal-signed terms several times the size of the rest, whose
+    rounding errors the tolerance, which is relative to the expert's whole gradient, is not made for.)"""
+    from paper_2103_13262_amd.synth import bf16_bits_to_f32, f32_to_bf16_bits
+
+    assert w.k == 1 and w.dtype == "bf16" and sum(counts) == w.N and len(counts) == w.E <= w.d
+    inputs = make_inputs(w)
+    expert = np.repeat(np.arange(w.E), counts)
+    np.random.default_rng(w.seed).shuffle(expert)
+    X = bf16_bits_to_f32(inputs["X"]).copy()
+    X[:, :w.E] = 0.0
+    X[np.arange(w.N), expert] = 1.0
+    Wg = np.zeros((w.d, w.E), np.float32)
+    Wg[np.arange(w.E), np.arange(w.E)] = 1.0
+    inputs["X"], inputs["Wg"] = f32_to_bf16_bits(X), f32_to_bf16_bits(Wg)
+    inputs["bg"] = np.zeros(w.E, np.float32)
+    return inputs
+
+
+@pytest.mark.parametrize("d,h", [(64, 128), (512, 1024)])
+def test_row_counts_at_the_size_class_boundaries(d, h):
+    """The row products compute an expert's whole blocks of 256 rows and its last piece of at most 128 rows in
+    different tile shapes: experts with 0, 1, 128, 129, 256, 257, 384 and 385 rows sit on every side of those
+    limits (one narrow shape, where a wide tile is mostly columns that do not exist, and one with several tiles)."""
+    counts = [0, 1, 128, 129, 256, 257, 384, 385]
+    w = Workload(f"class_boundaries_{d}x{h}", sum(counts), d, h, len(counts), 1, "bf16", 0.0, 44)
+    inputs = _routed_inputs(w, counts)
+    run = GpuRun(w, inputs).run(backward=False)
+    np.testing.assert_array_equal(run.plan_arrays()["counts"], counts)
+    _full_check(w, inputs=inputs)
 
 
 def test_accumulate_adds_to_existing_gradients():
