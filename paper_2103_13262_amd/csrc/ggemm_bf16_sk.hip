@@ -858,6 +858,7 @@ __device__ __forceinline__ void ggemm_classes(const GemmArgs& g, int ntn_big, in
     const int W = gridDim.x >> 3;
     const long Tb = (long)g.cls[kClsPBig * (g.E + 1) + g.E] * ntn_big, Ts = (long)g.cls[kClsPSmall * (g.E + 1) + g.E] * ntn_small;
     if (Ts == 0) { ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big); return; }
+    if (Tb == 0) { ggemm_sk_body<KIND, 1, 8, 4, 2, 3, 32, 2>(g, 0, ntn_small); return; }
     if (g.K >= 2 * kMinSplitDepth && W >= 2 && Tb < 8L * W) {
         // Deep reductions with less than a round of tiles are cut into equal pieces over the workgroups, so a second
         // phase for the last pieces would leave most workgroups idle: the two classes run side by side instead, on
@@ -865,8 +866,8 @@ __device__ __forceinline__ void ggemm_classes(const GemmArgs& g, int ntn_big, in
         // 256 x 256 tile moves).  (With whole rounds of tiles the shares would have to match the classes' times more
         // closely than such an estimate can: measured 7 % slower on a large problem.)
         const long cs = Ts * 5, cb = Tb * 4;
-        int ws = Tb == 0 ? W : (int)((W * cs + (cs + cb) / 2) / (cs + cb));
-        ws = Tb == 0 ? W : ws < 1 ? 1 : ws > W - 1 ? W - 1 : ws;
+        int ws = (int)((W * cs + (cs + cb) / 2) / (cs + cb));
+        ws = ws < 1 ? 1 : ws > W - 1 ? W - 1 : ws;
         ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big, 0, W - ws);
         ggemm_sk_body<KIND, 1, 8, 4, 2, 3, 32, 2>(g, 0, ntn_small, W - ws, ws);   // (a workgroup runs one of the two)
         return;
