@@ -74,7 +74,8 @@ __device__ __forceinline__ int swap13(int c) { return (c & ~10) | ((c & 2) << 2)
 template <int BK> __device__ __forceinline__ int swz(int r)
 {
     if constexpr (BK == 32) return ((r >> 1) & 3) ^ ((r >> 3) & 1);
-    else return (r >> 1) & 7;
+    else if constexpr (BK == 64) return (r >> 1) & 7;
+    else return r & 15;   // 256-byte rows: every row starts at bank 0, 16 rows take 16 different chunk positions
 }
 
 // s_waitcnt vmcnt(N) only (export and LDS counters left at their maxima), gfx9 encoding.
@@ -852,9 +853,25 @@ __global__ __launch_bounds__(WM * WN * 64, 1) void ggemm_sk_kernel(GemmArgs g, i
 // The rows of every expert in two size classes, one after the other in one launch: whole blocks of 256 rows in
 // 256 x 256 tiles, then the experts' last pieces (at most 128 rows) in 128 x 512 tiles.  The main loop's pace is set by
 // the arrival of the operand blocks, not by what a tile holds, so a last piece costs half as much in tiles twice as wide.
-template <int KIND, int STAGES, int BK>
+// DEEP (chosen by the host for reductions shallower than 2 * kMinSplitDepth, which are never cut into pieces): the
+// last pieces in 128 x 128 tiles with 128-deep blocks instead.  A tile's time is its number of blocks times the
+// time a block takes to arrive, so the few last pieces, which get a phase of their own behind the big tiles, are
+// done in a quarter of the blocks, by four times as many workgroups.
+template <int KIND, int STAGES, int BK, bool DEEP>
 __device__ __forceinline__ void ggemm_classes(const GemmArgs& g, int ntn_big, int ntn_small)
 {
+    if constexpr (DEEP) {
+        ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big);
+        __syncthreads();   // the first class's last epilogue is done with the LDS before the second lays it out anew
+        // (only while the narrow tiles are at most one round: beyond that their number counts, not their length, and
+        // the wide ones are fewer - measured on a skewed load with 44 last pieces: 7 % slower with the narrow ones)
+        const int ntn_deep = (g.Nout + 127) / 128;
+        if ((long)g.cls[kClsPSmall * (g.E + 1) + g.E] * ntn_deep <= (long)gridDim.x)
+            ggemm_sk_body<KIND, 2, 4, 2, 1, 2, 128, 2>(g, 0, ntn_deep);
+        else
+            ggemm_sk_body<KIND, 1, 8, 4, 2, 3, 32, 2>(g, 0, ntn_small);
+        return;
+    }
     const int W = gridDim.x >> 3;
     const long Tb = (long)g.cls[kClsPBig * (g.E + 1) + g.E] * ntn_big, Ts = (long)g.cls[kClsPSmall * (g.E + 1) + g.E] * ntn_small;
     if (Ts == 0) { ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big); return; }
@@ -877,20 +894,20 @@ __device__ __forceinline__ void ggemm_classes(const GemmArgs& g, int ntn_big, in
     ggemm_sk_body<KIND, 1, 8, 4, 2, 3, 32, 2>(g, 0, ntn_small);
 }
 
-template <int KIND, int STAGES, int BK>
+template <int KIND, int STAGES, int BK, bool DEEP>
 __global__ __launch_bounds__(512, 1) void ggemm_cls_kernel(GemmArgs g, int ntn_big, int ntn_small)
 {
-    ggemm_classes<KIND, STAGES, BK>(g, ntn_big, ntn_small);
+    ggemm_classes<KIND, STAGES, BK, DEEP>(g, ntn_big, ntn_small);
 }
 
 // Two products that do not depend on each other in one launch: a rows kind, then the weight gradients with their
 // tiles handed out on demand.  A workgroup that runs out of tiles of the first product goes on with the second
 // instead of idling until the launch ends, and one launch gap is saved.  CLASSES: the rows kind in size classes
 // (as ggemm_cls_kernel), else in 64 x 256 tiles (many small experts).
-template <int KIND, bool CLASSES>
+template <int KIND, bool CLASSES, bool DEEP>
 __global__ __launch_bounds__(512, 1) void ggemm_pair_kernel(GemmArgs g1, int ntn1, int ntn1_small, GemmArgs g2, int ntm2, int ntn2)
 {
-    if constexpr (CLASSES) ggemm_classes<KIND, 2, 64>(g1, ntn1, ntn1_small);
+    if constexpr (CLASSES) ggemm_classes<KIND, 2, 64, DEEP>(g1, ntn1, ntn1_small);
     else ggemm_sk_body<KIND, 1, 8, 2, 1, 3, 64>(g1, 0, ntn1);
     __syncthreads();
     ggemm_sk_body<kColsT, 2, 4, 4, 2, 4, 32>(g2, ntm2, ntn2);
@@ -968,14 +985,17 @@ void launch_cfg(const GemmArgs& a, hipStream_t st)
 #endif
 }
 
-template <int KIND, int STAGES, int BK>
-void launch_cls(const GemmArgs& a, hipStream_t st)
+template <int KIND> using CfgWide = Cfg<KIND, 1, 8, 4, 2, 3, 32>;
+template <int KIND> using CfgDeep = Cfg<KIND, 2, 4, 2, 1, 2, 128>;
+
+template <int KIND, int STAGES, int BK, bool DEEP>
+void launch_cls_cfg(const GemmArgs& a, hipStream_t st)
 {
     using C1 = Cfg<KIND, 2, 4, 4, 2, STAGES, BK>;
-    using C2 = Cfg<KIND, 1, 8, 4, 2, 3, 32>;
+    using C2 = CfgWide<KIND>;
     static_assert((size_t)C2::BM * C2::BN * 4 <= kPartialBytesPerWg, "partial-sum buffer");
-    constexpr int SMEM = C1::SMEM > C2::SMEM ? C1::SMEM : C2::SMEM;
-    auto kern = ggemm_cls_kernel<KIND, STAGES, BK>;
+    constexpr int SMEM = std::max({C1::SMEM, C2::SMEM, DEEP ? CfgDeep<KIND>::SMEM : 0});
+    auto kern = ggemm_cls_kernel<KIND, STAGES, BK, DEEP>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess) return;
@@ -987,6 +1007,13 @@ void launch_cls(const GemmArgs& a, hipStream_t st)
     b.trace = nullptr;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(512), SMEM, st, b, (a.Nout + C1::BN - 1) / C1::BN,
                        (a.Nout + C2::BN - 1) / C2::BN);
+}
+
+template <int KIND, int STAGES, int BK>
+void launch_cls(const GemmArgs& a, hipStream_t st)
+{
+    if (a.K < 2 * kMinSplitDepth) launch_cls_cfg<KIND, STAGES, BK, true>(a, st);
+    else launch_cls_cfg<KIND, STAGES, BK, false>(a, st);
 }
 
 template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
@@ -1013,14 +1040,14 @@ template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
 }  // namespace sk
 
 namespace sk {
-template <int KIND, bool CLASSES>
+template <int KIND, bool CLASSES, bool DEEP>
 void launch_pair_cfg(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
 {
     using C1 = std::conditional_t<CLASSES, Cfg<KIND, 2, 4, 4, 2, 2, 64>, Cfg<KIND, 1, 8, 2, 1, 3, 64>>;
-    using C1s = Cfg<KIND, 1, 8, 4, 2, 3, 32>;
+    using C1s = CfgWide<KIND>;
     using C2 = Cfg<kColsT, 2, 4, 4, 2, 4, 32>;
-    constexpr int SMEM = std::max({C1::SMEM, CLASSES ? C1s::SMEM : 0, C2::SMEM});
-    auto kern = ggemm_pair_kernel<KIND, CLASSES>;
+    constexpr int SMEM = std::max({C1::SMEM, CLASSES ? C1s::SMEM : 0, CLASSES && DEEP ? CfgDeep<KIND>::SMEM : 0, C2::SMEM});
+    auto kern = ggemm_pair_kernel<KIND, CLASSES, DEEP>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess) return;
@@ -1038,8 +1065,9 @@ void launch_pair_cfg(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
 
 template <int KIND> void launch_pair_kind(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
 {
-    if (rows.M < 96L * rows.E) launch_pair_cfg<KIND, false>(rows, cols, st);   // as in launch_kind
-    else launch_pair_cfg<KIND, true>(rows, cols, st);
+    if (rows.M < 96L * rows.E) launch_pair_cfg<KIND, false, false>(rows, cols, st);   // as in launch_kind
+    else if (rows.K < 2 * kMinSplitDepth) launch_pair_cfg<KIND, true, true>(rows, cols, st);
+    else launch_pair_cfg<KIND, true, false>(rows, cols, st);
 }
 }  // namespace sk
 
