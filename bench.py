@@ -67,7 +67,7 @@ def cpu_baseline(w, inputs, n_tokens):
 # file (FETCH_SIZE, then WRITE_SIZE), each divided by what the same counter reads for a plain 1 GiB copy
 # (0.500 and 1.000 of the true KiB); profiles/C1_hbm_traffic_pmc.md holds the commands and per-kernel figures.
 # Counters cannot be read from inside a run, so this is the stored measurement, not a live one.
-MEASURED_HBM_BYTES_PER_GEMM_LAUNCH = {"C1": 574.3e6}
+MEASURED_HBM_BYTES_PER_GEMM_LAUNCH = {"C1": 568.6e6}
 
 
 def main():
