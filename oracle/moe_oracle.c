@@ -174,6 +174,8 @@ int orc_plan(int64_t M, int32_t E, const int32_t *idx /*[M]*/, int32_t *counts /
  *   Y[n_tok,d], dX[n_tok,d]           rows follow `tokens`
  *   idx[n_tok,k], w[n_tok,k], dl[n_tok,k]
  *   Zo[n_tok,k,h] pre-activation, Oo[n_tok,k,d] expert outputs E_i(x)
+ *   Go[n_tok,k,h] GeLU(z), dOo[n_tok,k,d] dL/dE_i(x) = w_i dy, dZo[n_tok,k,h] dL/dz,
+ *   dXo[n_tok,k,d] the expert's share of dL/dx (W1 dz): the values the loop holds per slot, copied out
  *   dW1[n_track,d,h], dW2[n_track,h,d] accumulated over the listed tokens (zeroed here)
  *   db1[n_track,h], db2[n_track,d]    likewise, gradients of the expert biases
  *   dWg[d,E], dbg[E]                  accumulated over the listed tokens (zeroed here)
@@ -181,7 +183,8 @@ int orc_plan(int64_t M, int32_t E, const int32_t *idx /*[M]*/, int32_t *counts /
 int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const int32_t *track,
               int32_t n_track, int32_t only_tracked, double *Y, double *dX, int32_t *idx_out,
               double *w_out, double *dl_out, double *Zo, double *Oo, double *dW1, double *dW2,
-              double *dWg, double *dbg, double *db1, double *db2)
+              double *dWg, double *dbg, double *db1, double *db2, double *Go, double *dOo, double *dZo,
+              double *dXo)
 {
     const int d = p->d, h = p->h, E = p->E, k = p->k, dt = p->dtype;
     if (k < 1 || k > E) return -1;
@@ -261,6 +264,7 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
             for (int i = 0; i < d; ++i) y[i] = w[j] * oj[i] + y[i];
             if (Zo) memcpy(Zo + ((size_t)n * k + j) * h, zj, sizeof(double) * (size_t)h);
             if (Oo) memcpy(Oo + ((size_t)n * k + j) * d, oj, sizeof(double) * (size_t)d);
+            if (Go) memcpy(Go + ((size_t)n * k + j) * h, gj, sizeof(double) * (size_t)h);
         }
         if (Y) memcpy(Y + (size_t)n * d, y, sizeof(double) * (size_t)d);
         if (!backward) continue;
@@ -317,6 +321,7 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
             const size_t w1o = (size_t)e * dh, w2o = (size_t)e * dh;
             const double *zj = z + (size_t)j * h, *gj = g + (size_t)j * h;
             for (int i = 0; i < d; ++i) dout[i] = w[j] * dy[i];       /* dL/do_j */
+            if (dOo) memcpy(dOo + ((size_t)n * k + j) * d, dout, sizeof(double) * (size_t)d);
             if (db2 && s >= 0)                                        /* o = ... + b2 */
                 for (int i = 0; i < d; ++i) db2[(size_t)s * d + i] += dout[i];
             /* o = W2^T g : dg = W2 dout ; dW2 += g (x) dout */
@@ -330,6 +335,7 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
                     for (int i = 0; i < d; ++i) row[i] += gj[c] * dout[i];
                 }
             }
+            if (dZo) memcpy(dZo + ((size_t)n * k + j) * h, dz, sizeof(double) * (size_t)h);
             if (db1 && s >= 0)                                        /* z = ... + b1 */
                 for (int c = 0; c < h; ++c) db1[(size_t)s * h + c] += dz[c];
             /* z = W1^T x : dW1 += x (x) dz ; dx += W1 dz */
@@ -338,6 +344,7 @@ int orc_layer(const orc_problem *p, const int32_t *tokens, int32_t n_tok, const 
                 double acc = 0.0;
                 for (int c = 0; c < h; ++c) acc += ld(p->W1, dt, w1o + (size_t)i * h + c) * dz[c];
                 dx[i] += acc;
+                if (dXo) dXo[((size_t)n * k + j) * d + i] = acc;
                 if (dW1 && s >= 0) {
                     double *row = dW1 + (size_t)s * dh + (size_t)i * h;
                     for (int c = 0; c < h; ++c) row[c] += x[i] * dz[c];

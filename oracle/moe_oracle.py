@@ -149,6 +149,10 @@ def layer(p: OracleProblem, tokens=None, track=None, only_tracked=False, want_in
     dl = alloc("dl", (nt, p.k), full and backward)
     Z = alloc("Z", (nt, p.k, p.h), want_internals and full)
     O = alloc("O", (nt, p.k, p.d), want_internals and full)
+    G = alloc("H", (nt, p.k, p.h), want_internals and full)
+    dO = alloc("dO", (nt, p.k, p.d), want_internals and full and backward)
+    dZ = alloc("dZ", (nt, p.k, p.h), want_internals and full and backward)
+    dXs = alloc("dXs", (nt, p.k, p.d), want_internals and full and backward)
     dW1 = alloc("dW1", (nslots, p.d, p.h), backward and want_dw)
     dW2 = alloc("dW2", (nslots, p.h, p.d), backward and want_dw)
     dWg = alloc("dWg", (p.d, p.E), full and backward)
@@ -158,7 +162,7 @@ def layer(p: OracleProblem, tokens=None, track=None, only_tracked=False, want_in
     rc = _load().orc_layer(C.byref(p._c), _ptr(tokens), C.c_int32(nt), _ptr(trk), C.c_int32(ntrk),
                            C.c_int32(1 if only_tracked else 0), _ptr(Y), _ptr(dX), _ptr(idx), _ptr(w),
                            _ptr(dl), _ptr(Z), _ptr(O), _ptr(dW1), _ptr(dW2), _ptr(dWg), _ptr(dbg), _ptr(db1),
-                           _ptr(db2))
+                           _ptr(db2), _ptr(G), _ptr(dO), _ptr(dZ), _ptr(dXs))
     if rc:
         raise ValueError(f"orc_layer failed ({rc})")
     out["tokens"] = tokens

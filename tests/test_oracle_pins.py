@@ -504,3 +504,70 @@ def test_balance_stats_closed_forms_and_library_softmax():
     f1, p1, l1 = balance_stats(hot, np.full((N, 1), 3), E)
     assert f1[3] == 1.0 and abs(p1[3] - 1.0) < 1e-12 and abs(l1 - E) < 1e-10
 
+
+
+# ------------------------------------------------------------------ the per-slot values the loop holds (H, dL/dE_i, dL/dz, W1 dz)
+def test_per_slot_intermediates_of_a_single_expert_are_the_dense_network_s():
+    # E = 1, k = 1: the values per slot are the hidden activations and gradients of the dense FFN (numpy + scipy)
+    p = _rand_problem(31, N=9, d=5, h=7, E=1, k=1)
+    out = orc.layer(p, want_internals=True)
+    X, W1, W2, dY = p.X, p.W1[0], p.W2[0], p.dY
+    Z = X @ W1
+    dZ = (dY @ W2.T) * _gelu_grad(Z)
+    np.testing.assert_allclose(out["H"][:, 0], _gelu(Z), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(out["dO"][:, 0], dY, rtol=0, atol=0)                  # w = 1 exactly
+    np.testing.assert_allclose(out["dZ"][:, 0], dZ, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(out["dXs"][:, 0], dZ @ W1.T, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("score_all", [False, True])
+def test_per_slot_intermediates_follow_their_definitions_slot_by_slot(score_all):
+    # general routing: every slot (t, j) with expert e = idx[t, j] against the dense expression of that one expert
+    # on that one token, and the slots' shares of dX add up to dX minus the gate's share
+    p0 = _rand_problem(32, N=11, d=5, h=6, E=4, k=3)
+    p = orc.OracleProblem(p0.X, p0.Wg, p0.W1, p0.W2, 3, bg=p0.bg, dY=p0.dY, score_all=score_all)
+    out = orc.layer(p, want_internals=True)
+    idx, w = out["idx"], out["w"]
+    for t in range(p.N):
+        for j in range(p.k):
+            e = idx[t, j]
+            z = p.X[t] @ p.W1[e]
+            do = w[t, j] * p.dY[t]
+            dz = (p.W2[e] @ do) * _gelu_grad(z)
+            np.testing.assert_allclose(out["Z"][t, j], z, rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(out["H"][t, j], _gelu(z), rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(out["O"][t, j], _gelu(z) @ p.W2[e], rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(out["dO"][t, j], do, rtol=1e-15, atol=0)
+            np.testing.assert_allclose(out["dZ"][t, j], dz, rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(out["dXs"][t, j], p.W1[e] @ dz, rtol=1e-12, atol=1e-13)
+    _, _, logits = orc.gate(p)
+    dL = np.zeros((p.N, p.E))
+    np.put_along_axis(dL, idx, out["dl"], axis=1)
+    if score_all:
+        S = (w * np.einsum("td,tjd->tj", p.dY, out["O"])).sum(1, keepdims=True)
+        dense = -softmax(logits, axis=1) * S
+        np.put_along_axis(dense, idx, 0.0, axis=1)
+        dL += dense
+    np.testing.assert_allclose(out["dXs"].sum(1) + dL @ p.Wg.T, out["dX"], rtol=1e-11, atol=1e-12)
+
+
+# ------------------------------------------------------------------ the dense per-expert statement (oracle/moe_expert_dense.py)
+@pytest.mark.parametrize("bias", [False, True])
+def test_dense_expert_segment_equals_the_per_token_oracle(bias):
+    from oracle.moe_expert_dense import expert_segment
+
+    p0 = _rand_problem(41, N=40, d=5, h=7, E=4, k=2)
+    g = np.random.default_rng(41)
+    b1, b2 = (g.standard_normal((4, 7)), g.standard_normal((4, 5))) if bias else (None, None)
+    p = orc.OracleProblem(p0.X, p0.Wg, p0.W1, p0.W2, 2, bg=p0.bg, dY=p0.dY, b1=b1, b2=b2)
+    out = orc.layer(p, want_internals=True)
+    idx, w = out["idx"], out["w"]
+    for e in range(p.E):
+        t, j = np.nonzero(idx == e)                      # the expert's assignments in ascending assignment order
+        assert t.size > 0
+        seg = expert_segment(p.X[t], p.W1[e], p.W2[e], w[t, j], p.dY[t], None if b1 is None else b1[e],
+                             None if b2 is None else b2[e])
+        for name, key in (("Z", "Z"), ("H", "H"), ("O", "O"), ("dO", "dO"), ("dZ", "dZ"), ("dXs", "dXs")):
+            np.testing.assert_allclose(seg[name], out[key][t, j], rtol=1e-12, atol=1e-13, err_msg=name)
+        for name in ("dW1", "dW2", "db1", "db2"):
+            np.testing.assert_allclose(seg[name], out[name][e], rtol=1e-11, atol=1e-12, err_msg=name)
