@@ -25,11 +25,15 @@
  *
  * All matrices are dense row-major.  Every pointer named "device" must be device
  * memory of the current HIP device, 16-byte aligned, owned by the caller for the
- * whole call and until the stream work has completed.  The library allocates
- * nothing, keeps no pointer after a call returns and has no global state besides
- * the thread-local error string.  All work is enqueued on `stream` (a hipStream_t
+ * whole call and until the stream work has completed.  The library allocates no
+ * device memory and keeps no pointer after a call returns.  Its state, all of it
+ * behind locks: the thread-local error string; per device, which kernels have had
+ * their LDS limit raised and the device's compute-unit count (filled in on first
+ * use); the event pool of the optional per-kernel timing (moe_profile_*: the one
+ * place that creates HIP events).  All work is enqueued on `stream` (a hipStream_t
  * passed as void*, NULL = the null stream); no call synchronises with the host or
- * copies anything to the host.  Calls return a status; nothing throws or aborts.
+ * copies anything to the host, except moe_check_status and moe_profile_read, which
+ * say so.  Calls return a status; nothing throws or aborts.
  * The calls enqueue kernels only (no memset or copy nodes), so a sequence of them
  * may be captured in a HIP graph once each has run once on the device outside a
  * capture (the first launch of some kernels sets a function attribute); replays
@@ -49,9 +53,11 @@ typedef enum {
     MOE_OK = 0,
     MOE_ERR_INVALID_ARG = -1, /* null required pointer, misaligned pointer, N<0, k<1, k>E, ...  */
     MOE_ERR_UNSUPPORTED = -2, /* d or h not a multiple of 32, E>1024, k>8, unknown dtype,
-                                 non-zero reserved field, expert bias given                  */
+                                 non-zero reserved field, score_all with the standalone
+                                 backward calls                                              */
     MOE_ERR_WORKSPACE = -3,   /* workspace smaller than moe_workspace_bytes()                 */
-    MOE_ERR_HIP = -4          /* a kernel launch reported an error                            */
+    MOE_ERR_HIP = -4          /* a kernel launch (or its set-up: a function attribute, a device
+                                 query) reported an error; moe_last_error() has the text      */
 } moe_status_t;
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
@@ -81,7 +87,8 @@ typedef struct {
  * moe_forward / moe_backward read.  M = N*k assignments, a = t*k + j. */
 typedef struct {
     int32_t *topk_idx; /* [N,k] expert of slot j of token t, slots in descending logit order  */
-    float *topk_w;     /* [N,k] combine weight (score) of that slot; each row sums to 1       */
+    float *topk_w;     /* [N,k] combine weight (score) of that slot; a row sums to 1 (less than
+                          1 with desc->score_all)                                            */
     int32_t *counts;   /* [E]   rows received by each expert                                  */
     int32_t *offsets;  /* [E+1] exclusive prefix sum of counts; offsets[E] = M                */
     int32_t *pos;      /* [M]   assignment a -> row of the expert-contiguous buffers          */
@@ -138,6 +145,19 @@ moe_status_t moe_backward(const moe_desc_t *desc, const moe_plan_t *plan, const 
                           void *dW1, void *dW2, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The status word of a workspace, copied to the host: 0, or 1 if since the last moe_plan on this workspace a
+ * grouped-product workgroup's bounded wait for another workgroup's partial sum ran out (then the results of those
+ * calls are invalid and moe_last_error() says so).  The persistent grouped-product kernels hand partial sums from
+ * one workgroup to the next and assume that all of a launch's workgroups (one per compute unit) are resident
+ * together, which holds when nothing else occupies the GPU's compute units for long; a caller that runs other
+ * kernels beside these on other streams should check the word.
+ * WAITS for the work enqueued on `stream` and copies 4 bytes to the host (one of the two calls that synchronise).
+ *   status: host int32, written.
+ */
+moe_status_t moe_check_status(const moe_desc_t *desc, const void *workspace, size_t workspace_bytes, void *stream,
+                              int32_t *status);
+
+/*
  * Load-balance monitor of the batch routed by the last moe_plan on this workspace (the paper leaves
  * a load-balance monitor to future work, Section 6; these are the statistics one is built from).
  * Needs desc->balance_stats or desc->score_all.
@@ -182,8 +202,8 @@ moe_status_t moe_bias_backward(const moe_desc_t *desc, const moe_plan_t *plan, f
  *                         + gate path), dWg[:,e] (+)= sum over assignments of e of dl * x, dbg likewise.
  *                         Wg [d,E], Xs [M,d] (as written by moe_scatter), dXs [M,d], dl [M] -> dX [N,d] dtype,
  *                         dWg [d,E] grad_dtype and dbg [E] float (or NULL), written or accumulated per
- *                         desc->accumulate.  Needs a workspace of moe_workspace_bytes() for its fixed-order
- *                         reduction; the workspace of moe_plan may be used.
+ *                         desc->accumulate.  Needs the workspace that moe_plan wrote for this plan (it reads the table of
+ *                         64-row pieces there and keeps its fixed-order reduction there).
  * With N == 0 nothing is launched except that moe_scatter_backward still writes dWg / dbg (zeros, or
  * leaves them when accumulating).
  */
@@ -201,9 +221,7 @@ moe_status_t moe_scatter_backward(const moe_desc_t *desc, const moe_plan_t *plan
  * expert outputs before the weighted gather (these four are valid after moe_forward);
  * "dYs" [M,d], "dZ" [M,h], "dXs" [M,d] (dtype elements) and "dl" [M] float, the gradient of the
  * selected logits (valid after moe_backward).  Rows are in expert-contiguous order (row r holds
- * assignment perm[r]).  "status": one int32, cleared by moe_plan and set to 1 if a workgroup's
- * bounded wait for another workgroup's partial sum ever ran out (never, by construction; results
- * of that call are then invalid).  "clock": two int64 written by the last bf16 matrix-product launch,
+ * assignment perm[r]).  "status": the int32 that moe_check_status returns.  "clock": two int64 written by the last bf16 matrix-product launch,
  * shader cycles and ticks of the 100 MHz reference clock over the lifetime of one of its workgroups
  * (their ratio x 100 is the shader clock in MHz the launch ran at).  Returns MOE_ERR_INVALID_ARG for an
  * unknown name.
@@ -211,7 +229,8 @@ moe_status_t moe_scatter_backward(const moe_desc_t *desc, const moe_plan_t *plan
 moe_status_t moe_workspace_region(const moe_desc_t *desc, const char *name, size_t *offset, size_t *bytes);
 
 /*
- * Diagnostics: per-kernel timing with HIP events, off by default.  While enabled, every kernel
+ * Diagnostics: per-kernel timing with HIP events, off by default (the one stateful, allocating corner of the
+ * library: a process-wide switch and a pool of events behind a mutex).  While enabled, every kernel
  * group the three calls launch is bracketed by two events recorded on the caller's stream (this
  * creates events, the one place where the library allocates, and adds a few microseconds per
  * launch, so whole-step timings should be taken with it disabled).

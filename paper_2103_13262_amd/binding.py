@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe355.so")
 
 MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP = 0, -1, -2, -3, -4
 MOE_F32, MOE_BF16 = 0, 1
-EXPORTS = ("moe_workspace_bytes", "moe_workspace_region", "moe_plan", "moe_forward", "moe_backward",
+EXPORTS = ("moe_workspace_bytes", "moe_workspace_region", "moe_check_status", "moe_plan", "moe_forward", "moe_backward",
            "moe_bias_backward", "moe_balance_stats", "moe_scatter", "moe_gather", "moe_gather_backward", "moe_scatter_backward",
            "moe_last_error", "moe_profile_enable", "moe_profile_read")
 
@@ -73,6 +73,8 @@ def lib():
         L.moe_workspace_region.restype = C.c_int
         L.moe_workspace_region.argtypes = [C.POINTER(MoeDesc), C.c_char_p, C.POINTER(C.c_size_t),
                                            C.POINTER(C.c_size_t)]
+        L.moe_check_status.restype = C.c_int
+        L.moe_check_status.argtypes = [C.POINTER(MoeDesc), vp, C.c_size_t, vp, C.POINTER(C.c_int32)]
         L.moe_profile_enable.restype = C.c_int
         L.moe_profile_enable.argtypes = [C.c_int]
         L.moe_profile_read.restype = C.c_int
@@ -108,6 +110,13 @@ def moe_workspace_region(desc, name):
     off, n = C.c_size_t(0), C.c_size_t(0)
     _check(lib().moe_workspace_region(C.byref(desc), name.encode(), C.byref(off), C.byref(n)))
     return int(off.value), int(n.value)
+
+
+def moe_check_status(desc, workspace, workspace_bytes, stream=0):
+    """The workspace's status word (0 = fine); waits for the stream."""
+    out = C.c_int32(-1)
+    _check(lib().moe_check_status(C.byref(desc), _p(workspace), C.c_size_t(workspace_bytes), C.c_void_p(stream), C.byref(out)))
+    return int(out.value)
 
 
 def moe_profile_enable(on):

@@ -26,9 +26,9 @@ FLAGS = [
 SOURCE_FLAGS = {"gate_topk.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
-def _compile(src, extra):
+def _compile(src):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, *SOURCE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *SOURCE_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the packed-fp32 feature name; that warning is harmless
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -37,12 +37,10 @@ def _compile(src, extra):
     return obj, err
 
 
-def build_library(extra_flags=(), verbose=False):
-    """extra_flags: e.g. ["-DMOE355_DEV_TRACE"] for a development build whose grouped-GEMM launches
-    synchronise and print per-workgroup phase times to stderr (never the build that is benchmarked)."""
+def build_library(verbose=False):
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        results = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
+        results = list(ex.map(_compile, SOURCES))
     if verbose:
         for _, err in results:
             if err.strip():

@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/moe355.h"
 
 namespace moe {
@@ -50,16 +52,33 @@ struct WsLayout {
     size_t dense_bpart;  // [ceil(N/512)][E] float: and to dbg
     int dense_chunks;
     size_t WgT;       // [E][d] gate matrix transposed (written by the plan step for E > 32 and by the backward pass), element type = desc.dtype
-    size_t zeros;     // 1 KB of zeros (written by the plan step): source of masked reduction rows
-    size_t sk_flags;  // [kMaxPersistentWgs] int32, directly behind the zero page and zeroed with it: "partial sum ready"
-    size_t sk_error;  // int32 behind the flags, zeroed with them: set if a wait for a partial sum ran out
-    size_t sk_part;   // [kMaxPersistentWgs] fp32 tiles: partial sums of split output tiles (bf16 only)
+    size_t zeros;     // the control block (see Ctl below): 1 KB of zeros, source of masked reduction rows, then the control words
+    size_t sk_flags;  // [kSkPhases][kMaxPersistentWgs] int32 "partial sum ready", zeroed with the zero page
+    size_t sk_error;  // int32: set if a wait for a partial sum ran out
+    size_t sk_part;   // [kSkPhases][kMaxPersistentWgs] fp32 tiles: partial sums of split output tiles (bf16 only)
     size_t total;
     int nb;           // plan chunks = ceil(M / kPlanChunk)
     long dwg_pieces;  // upper bound of 64-row pieces over all experts: floor(M/64) + E
 };
 
-constexpr size_t kZeroedBytes = 1024 + kMaxPersistentWgs * sizeof(int32_t) + 256;  // zero page, flags, error word
+// A launch may run two products' worth of split tiles one after the other (the two size classes of the rows
+// kinds): each phase has partial-sum buffers and flags of its own, so a workgroup that is already in the second
+// phase never overwrites a partial sum of the first that its successor has not read yet.
+constexpr int kSkPhases = 2;
+// The control block of a workspace, in int32 words from its start.  The plan step zeroes all of it and then sets
+// by_expert and skewed; the grouped products read and update the rest.
+enum Ctl {
+    kCtlZeroPage = 0,                                          // 256 words of zeros
+    kCtlFlags = 256,                                           // [kSkPhases][kMaxPersistentWgs] "partial sum ready"
+    kCtlError = kCtlFlags + kSkPhases * kMaxPersistentWgs,     // status word: 1 if a bounded wait ran out
+    kCtlByExpert = kCtlError + 1,                              // 1: the weight gradients give every XCD whole experts
+    kCtlClock = kCtlError + 2,                                 // two int64: shader cycles, 100 MHz ticks (8-byte aligned)
+    kCtlSkewed = kCtlError + 6,                                // 1: the experts' sizes are strongly skewed
+    kCtlDyn = kCtlError + 8,                                   // [9] on-demand tile counters per XCD + workgroups finished
+    kCtlWords = kCtlError + 32
+};
+static_assert(kCtlClock % 2 == 0 && kCtlWords <= 1024, "clock words 8-byte aligned; one 1024-thread workgroup zeroes the block");
+constexpr size_t kZeroedBytes = kCtlWords * sizeof(int32_t);
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t dtype_size(int dt) { return dt == MOE_BF16 ? 2 : 4; }
 
@@ -101,16 +120,39 @@ inline WsLayout ws_layout(const moe_desc_t& D)
         L.dense_bpart = take((size_t)L.dense_chunks * D.E * sizeof(float));
     }
     L.zeros = take(kZeroedBytes);
-    L.sk_flags = L.zeros + 1024;
-    L.sk_error = L.sk_flags + kMaxPersistentWgs * sizeof(int32_t);
-    L.sk_part = take(D.dtype == MOE_BF16 ? kMaxPersistentWgs * kPartialBytesPerWg : 0);
+    L.sk_flags = L.zeros + kCtlFlags * sizeof(int32_t);
+    L.sk_error = L.zeros + kCtlError * sizeof(int32_t);
+    L.sk_part = take(D.dtype == MOE_BF16 ? (size_t)kSkPhases * kMaxPersistentWgs * kPartialBytesPerWg : 0);
     L.total = o;
     return L;
 }
 
 // ---- error reporting -------------------------------------------------------------------
 void set_error(const char* fmt, ...);
+// A launcher that could not launch (a function attribute was refused, no usable device): records the text and makes
+// the next check_launch on this thread return MOE_ERR_HIP.
+void fail_launch(const char* fmt, ...);
 moe_status_t check_launch(const char* what);
+constexpr int kMaxDevices = 64;   // per-device caches (function attributes, compute-unit counts) are indexed by the HIP device id
+int current_device();             // the calling thread's HIP device, or -1 (after fail_launch)
+moe_status_t check_desc(const moe_desc_t* D);   // host-side validation of a problem description (sets the error text)
+
+// Kernels whose dynamic LDS exceeds the default limit: the kernel's limit is raised once per device (the static
+// state is per kernel: one instance of this template each).  False after fail_launch.
+template <typename Kern> static bool allow_dynamic_lds(Kern kern, int bytes)
+{
+    static std::mutex mu;
+    static bool done[kMaxDevices] = {};
+    const int dev = current_device();
+    if (dev < 0) return false;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!done[dev]) {
+        const hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e != hipSuccess) { fail_launch("%d bytes of dynamic LDS refused on device %d: %s", bytes, dev, hipGetErrorString(e)); return false; }
+        done[dev] = true;
+    }
+    return true;
+}
 
 // ---- kernel launchers (each enqueues on `st`; operand shapes are validated by the callers) ----
 void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
@@ -161,8 +203,8 @@ struct GemmArgs {
     const int32_t* order;  // [E]
     const int32_t* cls;    // [kClsTables][E+1] size-class tables of the plan step, or NULL (bf16 row products only)
     const void* zeros;     // 1 KB of zeros
-    void* sk_part;         // partial-sum tiles, one per persistent workgroup
-    int32_t* sk_flags;     // one flag per persistent workgroup, all zero between launches
+    void* sk_part;         // partial-sum tiles, one per phase and persistent workgroup
+    int32_t* sk_flags;     // one flag per phase and persistent workgroup, all zero between launches
     int32_t* sk_error;
     const int32_t* by_expert;  // 1: the weight-gradient products give every XCD whole experts (decided by the plan step)
     long long* clock_probe;    // [2]: shader cycles and 100 MHz ticks of workgroup 0 of the last launch
@@ -171,8 +213,20 @@ struct GemmArgs {
     int on_demand;             // weight gradients: hand the tiles out from the counters whatever the sizes
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT
-    long long* trace; // development builds only: per-workgroup phase times (8 words per workgroup) or NULL
 };
+// Points the control-block fields of a GemmArgs at a workspace's control block.
+inline void set_control(GemmArgs& a, char* ws, const WsLayout& L)
+{
+    int32_t* ctl = (int32_t*)(ws + L.zeros);
+    a.zeros = ctl + kCtlZeroPage;
+    a.sk_part = ws + L.sk_part;
+    a.sk_flags = ctl + kCtlFlags;
+    a.sk_error = ctl + kCtlError;
+    a.by_expert = ctl + kCtlByExpert;
+    a.clock_probe = (long long*)(ctl + kCtlClock);
+    a.skewed = ctl + kCtlSkewed;
+    a.dyn_counters = ctl + kCtlDyn;
+}
 void launch_segment_sums(const moe_desc_t& D, const WsLayout& L, const void* src, int width, const int32_t* counts,
                          const int32_t* offsets, float* out, char* ws, hipStream_t st);
 void launch_ggemm_f32(const GemmArgs& a, hipStream_t st);
@@ -204,35 +258,5 @@ __device__ __forceinline__ float gelu_grad_f(float z)
     return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * __expf(-0.5f * z * z) * 0.39894228040143268f;
 }
 
-
-// Branch-free GeLU and GeLU' for the bf16 epilogues.  erf by the rational-exponential form of Abramowitz &
-// Stegun 7.1.26 (|error| <= 1.5e-7, far below bf16 resolution): erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2),
-// t = 1 / (1 + p x) for x >= 0, odd extension for x < 0.
-__device__ __forceinline__ float erf_fast(float x)
-{
-    const float ax = fabsf(x);
-    const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
-    float poly = fmaf(1.061405429f, t, -1.453152027f);
-    poly = fmaf(poly, t, 1.421413741f);
-    poly = fmaf(poly, t, -0.284496736f);
-    poly = fmaf(poly, t, 0.254829592f);
-    const float e = __expf(-ax * ax);
-    const float r = fmaf(-poly * t, e, 1.0f);
-    return copysignf(r, x);
-}
-__device__ __forceinline__ float gelu_fast(float z) { return 0.5f * z * (1.0f + erf_fast(z * 0.70710678118654752f)); }
-__device__ __forceinline__ float gelu_grad_fast(float z)
-{   // Phi(z) + z phi(z); the exponential of the erf formula at x = z / sqrt(2) is exp(-z^2 / 2), shared with phi
-    const float ax = fabsf(z) * 0.70710678118654752f;
-    const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
-    float poly = fmaf(1.061405429f, t, -1.453152027f);
-    poly = fmaf(poly, t, 1.421413741f);
-    poly = fmaf(poly, t, -0.284496736f);
-    poly = fmaf(poly, t, 0.254829592f);
-    const float e = __expf(-0.5f * z * z);
-    const float erf_abs = fmaf(-poly * t, e, 1.0f);
-    const float cdf = fmaf(0.5f, copysignf(erf_abs, z), 0.5f);
-    return fmaf(z * 0.39894228040143268f, e, cdf);
-}
 
 }  // namespace moe

@@ -497,11 +497,7 @@ static void launch_wide_mt(const moe_desc_t& D, const T* X, const T* WgT, const 
     constexpr int slab = (16 * MT + 64) * S * (int)sizeof(T), merge = 4 * kMaxK * 64 * (8 + 4);
     constexpr int smem = slab > merge ? slab : merge;      // the logit patch (16*MT x 64 doubles) is smaller than the slabs
     auto kern = gate_mfma_wide_kernel<T, MT>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) return;
-        attr_set = true;
-    }
+    if (!allow_dynamic_lds(kern, smem)) return;
     hipLaunchKernelGGL(kern, dim3((unsigned)((D.N + 16 * MT - 1) / (16 * MT))), dim3(256), smem, st, X, WgT, bg, D.N, D.d,
                        D.E, D.k, idx, w, logits);
 }

@@ -46,6 +46,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
 #include <type_traits>
 #include <utility>
 #include <vector>
@@ -193,14 +194,11 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-#ifdef MOE355_DEV_TRACE
-    long long tr[4] = {0, 0, 0, 0}, t_mark = wall_clock64(), t_begin = t_mark;
-    int tr_items = 0;
-#define TRACE_PHASE(i) { const long long now = wall_clock64(); tr[i] += now - t_mark; t_mark = now; }
-#else
-#define TRACE_PHASE(i)
-#endif
 
+    // split tiles of the last pieces' class use the second set of partial-sum buffers and flags: a workgroup that
+    // has moved on to that class must not overwrite what its successor has yet to read of the first
+    constexpr int kPhase = CLS == 2 ? 1 : 0;
+    const int sk_slot = kPhase * kMaxPersistentWgs + (int)blockIdx.x;
     float* patch = (float*)(smem + C::RING) + wave * (8 * PITCH);
     const float* act = (const float*)(smem + C::RING + C::PATCH_BYTES);
 
@@ -581,7 +579,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
     auto store_partial = [&]() {
         int tid_ = tid;
         asm volatile("" : "+v"(tid_));   // keeps the address arithmetic of this cold path out of the main loop's registers
-        char* const dst = (char*)g.sk_part + (size_t)blockIdx.x * kPartialBytesPerWg + tid_ * 16;
+        char* const dst = (char*)g.sk_part + (size_t)sk_slot * kPartialBytesPerWg + tid_ * 16;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -597,11 +595,11 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
                 }
         wait_vmcnt<0>();                       // this wave's partial sums have arrived ...
         __syncthreads();                       // ... and so have those of the other waves
-        if (tid == 0) __hip_atomic_store(g.sk_flags + blockIdx.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_store(g.sk_flags + sk_slot, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
     // Adds the partial sum of the workgroup just below (same XCD slot, one position lower).  The ring must be idle.
     auto add_predecessor = [&]() {
-        const int id = blockIdx.x - 8;
+        const int id = sk_slot - 8;
         if (tid == 0) {
             int spins = 0;
             while (__hip_atomic_load(g.sk_flags + id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 1) {
@@ -791,7 +789,6 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         if (have)
             for (int i = tid; i < 2 * kActEntries; i += NT) w[i] = act_entry<KIND>(i);
     }
-    TRACE_PHASE(0);
     while (have) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -807,23 +804,17 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
             // operations came later: wait for everything, then every wave may read ring slot 0.
             wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
-            TRACE_PHASE(1);
             if (tm_act == TM) main_loop(std::true_type{}, nk);
             else main_loop(std::false_type{}, nk);   // tail tiles skip the 32-row blocks that hold no valid row
             __builtin_amdgcn_s_waitcnt(0xc07f);
             __builtin_amdgcn_s_barrier();              // every wave is done reading the ring
         }
-        TRACE_PHASE(2);
         const Fin fin{cur.c_off, cur.b_off, cur.Mt, cur.Nt, cur.owner};
         if (cur.kb0 > 0) add_predecessor();   // the blocks before kb0 were summed by the workgroup just below
         have = next_item(cur);
         if (have) start_item(cur);
         if (fin.owner) epilogue(fin);
         else store_partial();
-        TRACE_PHASE(3);
-#ifdef MOE355_DEV_TRACE
-        ++tr_items;
-#endif
     }
     if constexpr (KIND == kColsT) {
         if (dynamic && tid == 0) {       // the last workgroup to finish leaves the counters at zero for the next launch
@@ -836,12 +827,6 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         g.clock_probe[0] = clock64() - probe_cycles0;
         g.clock_probe[1] = wall_clock64() - probe_ticks0;
     }
-#ifdef MOE355_DEV_TRACE
-    if (g.trace && tid == 0) {
-        long long* t = g.trace + (size_t)blockIdx.x * 8;
-        t[0] = tr[0]; t[1] = tr[1]; t[2] = tr[2]; t[3] = tr[3]; t[4] = tr_items; t[5] = t_begin; t[6] = wall_clock64(); t[7] = 1;
-    }
-#endif
 }
 
 template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
@@ -913,18 +898,24 @@ __global__ __launch_bounds__(512, 1) void ggemm_pair_kernel(GemmArgs g1, int ntn
     ggemm_sk_body<kColsT, 2, 4, 4, 2, 4, 32>(g2, ntm2, ntn2);
 }
 
-// Persistent workgroups of one launch: one per compute unit, a multiple of the 8 XCDs, at most kMaxPersistentWgs
-// (the workspace holds one partial-sum buffer per workgroup).
+// Persistent workgroups of one launch: one per compute unit of the current device, a multiple of the 8 XCDs, at most
+// kMaxPersistentWgs (the workspace holds one partial-sum buffer per workgroup and phase).  0 after fail_launch.
 static int persistent_wgs()
 {
-    static const int n = [] {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    static std::mutex mu;
+    static int cached[kMaxDevices] = {};
+    const int dev = current_device();
+    if (dev < 0) return 0;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!cached[dev]) {
+        int cus = 0;
+        const hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) { fail_launch("grouped GEMM: compute-unit count of device %d: %s", dev, hipGetErrorString(e)); return 0; }
         cus = cus / 8 * 8;
-        return cus > kMaxPersistentWgs ? kMaxPersistentWgs : cus;
-    }();
-    return n;
+        if (cus < 8) { fail_launch("grouped GEMM: device %d has fewer than 8 compute units", dev); return 0; }
+        cached[dev] = cus > kMaxPersistentWgs ? kMaxPersistentWgs : cus;
+    }
+    return cached[dev];
 }
 
 template <int KIND, int WM, int WN, int TM, int TN, int STAGES, int BK>
@@ -933,56 +924,12 @@ void launch_cfg(const GemmArgs& a, hipStream_t st)
     using C = Cfg<KIND, WM, WN, TM, TN, STAGES, BK>;
     static_assert((size_t)C::BM * C::BN * 4 <= kPartialBytesPerWg, "partial-sum buffer");
     auto kern = ggemm_sk_kernel<KIND, WM, WN, TM, TN, STAGES, BK>;
-    static bool attr_set = false;   // the LDS ring is larger than the default dynamic limit
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM) != hipSuccess)
-            return;   // launch skipped; the caller's hipGetLastError() reports the failure
-        attr_set = true;
-    }
+    if (!allow_dynamic_lds(kern, C::SMEM)) return;
     const int wgs = persistent_wgs();
-    if (wgs < 8) { set_error("grouped GEMM: no device with at least 8 compute units"); return; }
+    if (wgs < 8) return;
     const int ntn = (a.Nout + C::BN - 1) / C::BN;
     const int ntm = KIND == kColsT ? (a.K + C::BM - 1) / C::BM : 0;
-    GemmArgs b = a;
-#ifdef MOE355_DEV_TRACE
-    static long long* buf = nullptr;
-    if (!buf) (void)hipMalloc(&buf, 8 * sizeof(long long) * kMaxPersistentWgs);
-    b.trace = buf;
-    (void)hipMemsetAsync(buf, 0, 8 * sizeof(long long) * wgs, st);
-#endif
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(C::NT), C::SMEM, st, b, ntm, ntn);
-#ifdef MOE355_DEV_TRACE
-    {
-        std::vector<long long> h(8 * wgs);
-        (void)hipStreamSynchronize(st);
-        (void)hipMemcpy(h.data(), b.trace, h.size() * sizeof(long long), hipMemcpyDeviceToHost);
-        double ph[4] = {0, 0, 0, 0}, items = 0; long long tmin = 0, tmax = 0, emin = 0; int n = 0;
-        for (int i = 0; i < wgs; ++i) {
-            const long long* t = &h[8 * i];
-            if (!t[7]) continue;
-            if (!n || t[5] < tmin) tmin = t[5];
-            if (!n || t[6] > tmax) tmax = t[6];
-            if (!n || t[6] < emin) emin = t[6];
-            ++n;
-            for (int k = 0; k < 4; ++k) ph[k] += (double)t[k];
-            items += (double)t[4];
-        }
-        {   // the three workgroups that end last, and the one that ends first
-            std::vector<int> idx;
-            for (int i = 0; i < wgs; ++i) if (h[8 * i + 7]) idx.push_back(i);
-            std::sort(idx.begin(), idx.end(), [&](int a, int b) { return h[8 * a + 6] > h[8 * b + 6]; });
-            for (size_t k = 0; k < idx.size(); ++k) {
-                if (k >= 3 && k + 1 != idx.size()) continue;
-                const long long* t = &h[8 * idx[k]];
-                fprintf(stderr, "    wg %3d (xcd %d pos %2d) end %.1f us: items %lld setup %.1f wait %.1f mainloop %.1f finish %.1f\n", idx[k],
-                        idx[k] & 7, idx[k] >> 3, (t[6] - tmin) * 0.01, t[4], t[0] * 0.01, t[1] * 0.01, t[2] * 0.01, t[3] * 0.01);
-            }
-        }
-        fprintf(stderr, "[trace kind %d cfg %dx%dx%d] wgs %d span %.1f us (first done after %.1f) items/wg %.2f | per wg (us): setup %.2f "
-                "wait %.2f mainloop %.2f finish %.2f\n", KIND, C::BM, C::BN, BK, n, (tmax - tmin) * 0.01, (emin - tmin) * 0.01, items / n,
-                ph[0] / n * 0.01, ph[1] / n * 0.01, ph[2] / n * 0.01, ph[3] / n * 0.01);
-    }
-#endif
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(C::NT), C::SMEM, st, a, ntm, ntn);
 }
 
 template <int KIND> using CfgWide = Cfg<KIND, 1, 8, 4, 2, 3, 32>;
@@ -996,16 +943,10 @@ void launch_cls_cfg(const GemmArgs& a, hipStream_t st)
     static_assert((size_t)C2::BM * C2::BN * 4 <= kPartialBytesPerWg, "partial-sum buffer");
     constexpr int SMEM = std::max({C1::SMEM, C2::SMEM, DEEP ? CfgDeep<KIND>::SMEM : 0});
     auto kern = ggemm_cls_kernel<KIND, STAGES, BK, DEEP>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess) return;
-        attr_set = true;
-    }
+    if (!allow_dynamic_lds(kern, SMEM)) return;
     const int wgs = persistent_wgs();
-    if (wgs < 8) { set_error("grouped GEMM: no device with at least 8 compute units"); return; }
-    GemmArgs b = a;
-    b.trace = nullptr;
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(512), SMEM, st, b, (a.Nout + C1::BN - 1) / C1::BN,
+    if (wgs < 8) return;
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(512), SMEM, st, a, (a.Nout + C1::BN - 1) / C1::BN,
                        (a.Nout + C2::BN - 1) / C2::BN);
 }
 
@@ -1030,7 +971,7 @@ template <int KIND> void launch_kind(const GemmArgs& a, hipStream_t st)
     // Otherwise the rows kinds run in two size classes (launch_cls): an expert's last few rows in 128 x 512 tiles.
     if constexpr (KIND != kColsT) {
         if (a.M < 96L * a.E) { launch_cfg<KIND, 1, 8, 2, 1, 3, 64>(a, st); return; }
-        if (!a.cls) { set_error("grouped GEMM: the plan step's size-class tables are missing"); return; }
+        if (!a.cls) { fail_launch("grouped GEMM: the plan step's size-class tables are missing"); return; }
         if constexpr (KIND == kRowsNN) launch_cls<KIND, 4, 32>(a, st);
         else launch_cls<KIND, 2, 64>(a, st);
     } else {
@@ -1048,15 +989,10 @@ void launch_pair_cfg(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
     using C2 = Cfg<kColsT, 2, 4, 4, 2, 4, 32>;
     constexpr int SMEM = std::max({C1::SMEM, CLASSES ? C1s::SMEM : 0, CLASSES && DEEP ? CfgDeep<KIND>::SMEM : 0, C2::SMEM});
     auto kern = ggemm_pair_kernel<KIND, CLASSES, DEEP>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) != hipSuccess) return;
-        attr_set = true;
-    }
+    if (!allow_dynamic_lds(kern, SMEM)) return;
     const int wgs = persistent_wgs();
-    if (wgs < 8) { set_error("grouped GEMM: no device with at least 8 compute units"); return; }
+    if (wgs < 8) return;
     GemmArgs r = rows, c = cols;
-    r.trace = nullptr;  c.trace = nullptr;
     c.on_demand = 1;
     const int ntn1 = (r.Nout + C1::BN - 1) / C1::BN, ntn1s = (r.Nout + C1s::BN - 1) / C1s::BN;
     const int ntn2 = (c.Nout + C2::BN - 1) / C2::BN, ntm2 = (c.K + C2::BM - 1) / C2::BM;

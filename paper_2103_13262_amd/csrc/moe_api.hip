@@ -23,8 +23,35 @@ void set_error(const char* fmt, ...)
     va_end(ap);
 }
 
+static thread_local bool g_launch_failed = false;
+
+void fail_launch(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    g_launch_failed = true;
+}
+
+int current_device()
+{
+    int dev = -1;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        fail_launch("cannot tell the current HIP device (%s, id %d)", hipGetErrorString(e), dev);
+        return -1;
+    }
+    return dev;
+}
+
 moe_status_t check_launch(const char* what)
 {
+    if (g_launch_failed) {           // the text was set by fail_launch
+        g_launch_failed = false;
+        (void)hipGetLastError();
+        return MOE_ERR_HIP;
+    }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         set_error("%s: %s", what, hipGetErrorString(e));
@@ -73,7 +100,7 @@ struct ScopedTimer {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-static moe_status_t check_desc(const moe_desc_t* D)
+moe_status_t check_desc(const moe_desc_t* D)
 {
     if (!D) { set_error("desc is NULL"); return MOE_ERR_INVALID_ARG; }
     if (D->N < 0 || D->d < 1 || D->h < 1 || D->E < 1 || D->k < 1 || D->k > D->E) {
@@ -199,12 +226,28 @@ moe_status_t moe_workspace_region(const moe_desc_t* desc, const char* name, size
         {"Ys", L.Ys, M * desc->d * b}, {"dYs", L.dYs, M * desc->d * b}, {"dZ", L.dZ, M * desc->h * b},
         {"dXs", L.dXs, M * desc->d * b}, {"dl", L.dl, M * sizeof(float)},
         {"status", L.sk_error, sizeof(int32_t)},
-        {"clock", L.sk_error + 8, 2 * sizeof(long long)},
+        {"clock", L.zeros + kCtlClock * sizeof(int32_t), 2 * sizeof(long long)},
     };
     for (const auto& r : regions)
         if (!strcmp(r.n, name)) { *offset = r.off; *bytes = r.len; return MOE_OK; }
     set_error("unknown workspace region '%s'", name);
     return MOE_ERR_INVALID_ARG;
+}
+
+moe_status_t moe_check_status(const moe_desc_t* desc, const void* workspace, size_t workspace_bytes, void* stream,
+                              int32_t* status)
+{
+    g_err[0] = 0;
+    moe_status_t s;
+    if ((s = check_desc(desc)) != MOE_OK) return s;
+    if (!status) { set_error("status is NULL"); return MOE_ERR_INVALID_ARG; }
+    WsLayout L;
+    if ((s = check_ws(desc, workspace, workspace_bytes, &L)) != MOE_OK) return s;
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess) e = hipMemcpy(status, (const char*)workspace + L.sk_error, sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) { set_error("moe_check_status: %s", hipGetErrorString(e)); return MOE_ERR_HIP; }
+    if (*status) set_error("a grouped-product workgroup's bounded wait for a partial sum ran out: the results of the calls on this workspace since the last moe_plan are invalid");
+    return MOE_OK;
 }
 
 moe_status_t moe_plan(const moe_desc_t* desc, const void* X, const void* Wg, const float* bg, moe_plan_t* plan,
@@ -268,14 +311,7 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     a.tileP = (const int32_t*)(ws + L.tileP);
     a.order = (const int32_t*)(ws + L.order);
     a.cls = (const int32_t*)(ws + L.cls);
-    a.zeros = ws + L.zeros;
-    a.sk_part = ws + L.sk_part;
-    a.sk_flags = (int32_t*)(ws + L.sk_flags);
-    a.sk_error = (int32_t*)(ws + L.sk_error);
-    a.by_expert = (const int32_t*)(ws + L.sk_error) + 1;
-    a.clock_probe = (long long*)(ws + L.sk_error + 8);
-    a.skewed = (const int32_t*)(ws + L.sk_error) + 6;
-    a.dyn_counters = (int32_t*)(ws + L.sk_error + 32);
+    set_control(a, ws, L);
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
     a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h; a.bias = b1;
@@ -332,14 +368,7 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     a.tileP = (const int32_t*)(ws + L.tileP);
     a.order = (const int32_t*)(ws + L.order);
     a.cls = (const int32_t*)(ws + L.cls);
-    a.zeros = ws + L.zeros;
-    a.sk_part = ws + L.sk_part;
-    a.sk_flags = (int32_t*)(ws + L.sk_flags);
-    a.sk_error = (int32_t*)(ws + L.sk_error);
-    a.by_expert = (const int32_t*)(ws + L.sk_error) + 1;
-    a.clock_probe = (long long*)(ws + L.sk_error + 8);
-    a.skewed = (const int32_t*)(ws + L.sk_error) + 6;
-    a.dyn_counters = (int32_t*)(ws + L.sk_error + 32);
+    set_control(a, ws, L);
     a.out_f32 = D.grad_dtype == MOE_F32;
     a.accumulate = D.accumulate;
 

@@ -63,8 +63,8 @@ __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ id
                                                   int32_t* __restrict__ order, int32_t* __restrict__ cls,
                                                   int32_t* __restrict__ zeros)
 {
-    // page read in place of masked rows, and the flags of the persistent matrix-product kernels behind it
-    if (threadIdx.x < (int)(kZeroedBytes / 4)) zeros[threadIdx.x] = 0;
+    // the control block: the page read in place of masked rows and the control words of the grouped products
+    if (threadIdx.x < kCtlWords) zeros[threadIdx.x] = 0;
     __shared__ int s_cnt[kMaxE];
     __shared__ int s_wave[16];
     __shared__ int s_hist[kFusedHistInts];
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ id
     }
     // Can the weight-gradient products give every XCD whole experts (expert of rank r to XCD r%8, every other
     // group of eight reversed)?  Then each operand panel is fetched by one XCD only.  Only if the reduction blocks
-    // that each XCD would get stay within 10 % of the mean; the answer sits behind the status word.
+    // that each XCD would get stay within 10 % of the mean; the answer is control word kCtlByExpert.
     __shared__ int s_xcd[8];
     if (threadIdx.x < 8) s_xcd[threadIdx.x] = 0;
     __syncthreads();
@@ -158,12 +158,12 @@ __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ id
     if (threadIdx.x == 0) {
         int mx = 0, sum = 0;
         for (int x = 0; x < 8; ++x) { mx = max(mx, s_xcd[x]); sum += s_xcd[x]; }
-        zeros[kZeroedBytes / 4 - 63] = (E >= 8 && (long)mx * 80 <= (long)sum * 11) ? 1 : 0;
+        zeros[kCtlByExpert] = (E >= 8 && (long)mx * 80 <= (long)sum * 11) ? 1 : 0;
         // Strongly skewed sizes (largest expert above three times the mean): the weight-gradient products hand out
-        // their tiles on demand instead of in fixed rounds; the flag sits five words behind the one above.
+        // their tiles on demand instead of in fixed rounds; (control word kCtlSkewed).
         int big = 0;
         for (int i = 0; i < E; ++i) big = max(big, s_cnt[i]);
-        zeros[kZeroedBytes / 4 - 58] = (E >= 2 && (long)big * E > 3 * M) ? 1 : 0;
+        zeros[kCtlSkewed] = (E >= 2 && (long)big * E > 3 * M) ? 1 : 0;
     }
 }
 

@@ -24,9 +24,7 @@ def test_balance_stats_match_their_definition(w):
     from oracle.moe_balance import balance_stats
 
     inputs = make_inputs(w)
-    run = GpuRun(w, inputs)
-    run.desc = B.make_desc(w.N, w.d, w.h, w.E, w.k, run.desc.dtype, run.desc.grad_dtype, 0, 1 if w.score_all else 0, 1)
-    run.buf = B.MoeLayerBuffers(run.desc, run.device)
+    run = GpuRun(w, inputs, balance_stats=1)
     run.plan()
     frac = torch.full((w.E,), float("nan"), dtype=torch.float32, device=run.device)
     prob = torch.full((w.E,), float("nan"), dtype=torch.float32, device=run.device)
@@ -34,6 +32,7 @@ def test_balance_stats_match_their_definition(w):
     b = run.buf
     B.moe_balance_stats(run.desc, b.plan, frac, prob, loss, b.workspace, b.ws_bytes, b.stream())
     torch.cuda.synchronize()
+    run.check_guards()
     idx, _, logits = orc.gate(oracle_problem(w, inputs, dY=False))
     f, p, l = balance_stats(logits, idx, w.E)
     np.testing.assert_array_equal(frac.cpu().numpy(), f.astype(np.float32))          # ratios of exact counts

@@ -1,100 +1,136 @@
-"""GPU parity at the full sizes of the benchmark workloads, in the launch configuration bench.py
-times.  The oracle cannot run these whole in seconds, so:
+"""GPU parity at the full sizes of the benchmark workloads, in the launch configuration bench.py times.
+
+C1, C2, C3: against the WHOLE oracle output - every token, every expert, every intermediate, the gate gradients
+from the oracle itself - exactly as the small cases of test_gpu_parity.py are (the per-token fp64 oracle needs about
+25 s, 50 s and 7 s for them on 16 host threads).
+
+C4 (13 TFLOP per step: the per-token oracle would need half an hour):
   - indices, weights, counts, offsets, permutation: checked in full (the oracle's gate is cheap);
-  - Y, dX, dl: checked on a seeded sample of tokens the oracle computes one by one;
-  - dW1, dW2: checked in full for one or two experts (the oracle runs only the rows routed there);
-  - dWg, dbg: every token contributes, so they are checked through properties that hold at any
-    size: columns sum to zero over experts (the softmax Jacobian has zero row sums), k = 1 gives
-    exact zeros, and dWg equals Xs^T dl evaluated in fp64 from the dl the GPU produced (dl itself
-    being checked against the oracle on the sample).
+  - Y, dX, dl and the intermediates' rows: on a seeded sample of 64 tokens the oracle computes one by one;
+  - dW1, dW2: in full for the lightest, the median and the heaviest expert.  The first two from the per-token oracle
+    restricted to the rows routed there; the heaviest (14 thousand rows, 3 minutes that way) from the dense per-expert
+    statement of oracle/moe_expert_dense.py, which is first compared with the per-token oracle on the median expert
+    at this very shape;
+  - dWg, dbg: every token contributes, so they are checked through properties that hold at any size: columns sum to
+    zero over experts (the softmax Jacobian has zero row sums) and dWg equals Xs^T dl evaluated in fp64 from the dl the
+    GPU produced (dl itself being checked against the oracle on the sample).
 """
+import time
+
 import numpy as np
 import pytest
 
-from harness import TOL, GpuRun, check_plan_exact, oracle_problem, rel_err, to_numpy64
+from harness import GpuRun, Judge, check_plan_exact, oracle_problem, to_numpy64
 from paper_2103_13262_amd.synth import WORKLOADS, make_inputs
+from test_gpu_parity import _full_check
 
 pytestmark = pytest.mark.gpu
 
 
-def _check_fullsize(name, n_tokens, dw_experts):
-    import oracle as orc
+@pytest.mark.timeout(600)
+def test_c1_paper_shape_whole_oracle():
+    _full_check(WORKLOADS["C1"])
 
-    w = WORKLOADS[name]
-    print(f"[fullsize] {w}", flush=True)
-    inputs = make_inputs(w)
-    print("  inputs ready", flush=True)
-    run = GpuRun(w, inputs).run()
-    ref_plan = check_plan_exact(run, inputs)
-    counts = ref_plan["counts"]
-    print(f"  routing exact; rows/expert max {counts.max()} median {int(np.median(counts))} min {counts.min()} "
-          f"empty {int((counts == 0).sum())}", flush=True)
-    tol = TOL[w.dtype]
-    p = oracle_problem(w, inputs)
 
-    toks = np.sort(np.random.default_rng(w.seed + 99).choice(w.N, size=n_tokens, replace=False)).astype(np.int32)
-    ref = orc.layer(p, tokens=toks, want_dw=False)
-    errs = {"Y": rel_err(to_numpy64(run.Y[toks.tolist()]), ref["Y"]),
-            "dX": rel_err(to_numpy64(run.dX[toks.tolist()]), ref["dX"])}
-    dl_gpu = run.region("dl").reshape(w.N, w.k)
-    if w.k > 1:
-        errs["dl"] = rel_err(dl_gpu[toks], ref["dl"])
-    else:
-        assert not np.any(dl_gpu) and not np.any(to_numpy64(run.dWg)) and not np.any(to_numpy64(run.dbg)[:w.E])
-    print("  sampled tokens:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
-
-    # weight gradients of selected experts, over all rows routed to them
-    nonempty = np.nonzero(counts > 0)[0]
-    by_count = nonempty[np.argsort(counts[nonempty], kind="stable")]
-    picks = {"lightest": by_count[0], "median": by_count[len(by_count) // 2], "heaviest": by_count[-1]}
-    for which in dw_experts:
-        e = int(picks[which])
-        rows_tok = np.unique(ref_plan["perm"][ref_plan["offsets"][e]:ref_plan["offsets"][e + 1]] // w.k).astype(np.int32)
-        r = orc.layer(p, tokens=rows_tok, track=np.array([e], np.int32), only_tracked=True)
-        # The floor of the error metric is the RMS of this expert's own block.  With fewer than 64 rows an
-        # element is a sum of few products of bf16-rounded operands (H, dYs, dZ: 2^-8 each) whose size varies
-        # strongly from element to element, and the worst of d*h elements exceeds 2e-2 of the block RMS for
-        # any bf16-operand product; such blocks are held to twice the bound.
-        slack = 2.0 if (w.dtype == "bf16" and counts[e] < 64) else 1.0
-        errs[f"dW1[{which} e={e} rows={counts[e]}]"] = rel_err(to_numpy64(run.dW1[e]), r["dW1"][0]) / slack
-        errs[f"dW2[{which} e={e} rows={counts[e]}]"] = rel_err(to_numpy64(run.dW2[e]), r["dW2"][0]) / slack
-        print(f"  dW of expert {e} ({which}, {counts[e]} rows) checked", flush=True)
-    for e in np.nonzero(counts == 0)[0]:
-        assert not np.any(to_numpy64(run.dW1[e])) and not np.any(to_numpy64(run.dW2[e]))
-
-    # gate gradient through properties
-    if w.k > 1:
-        dWg, dbg = to_numpy64(run.dWg), to_numpy64(run.dbg)[:w.E]
-        Xw = orc.bf16_bits_to_f64(inputs["X"]) if w.dtype == "bf16" else inputs["X"].astype(np.float64)
-        flat_e = ref_plan["idx"].reshape(-1)
-        expect = np.zeros((w.d, w.E))
-        for e in range(w.E):
-            a = np.nonzero(flat_e == e)[0]
-            expect[:, e] = Xw[a // w.k].T @ dl_gpu.reshape(-1)[a]
-        errs["dWg vs Xs^T dl"] = rel_err(dWg, expect)
-        errs["dbg vs sum dl"] = rel_err(dbg, np.bincount(flat_e, weights=dl_gpu.reshape(-1), minlength=w.E))
-        scale = np.sqrt(np.mean(dWg * dWg))
-        assert np.max(np.abs(dWg.sum(1))) <= 0.05 * scale * np.sqrt(w.E)     # columns cancel over experts
-    print("  all:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
-    for k_, v in errs.items():
-        assert v <= tol, (k_, v, tol)
+@pytest.mark.timeout(900)
+def test_c2_skewed_load_whole_oracle():
+    _full_check(WORKLOADS["C2"])
 
 
 @pytest.mark.timeout(600)
-def test_c1_paper_shape():
-    _check_fullsize("C1", 16, ["lightest"])
-
-
-@pytest.mark.timeout(600)
-def test_c2_skewed_load():
-    _check_fullsize("C2", 16, ["lightest", "median"])
-
-
-@pytest.mark.timeout(600)
-def test_c3_many_small_experts():
-    _check_fullsize("C3", 64, ["lightest", "heaviest"])
+def test_c3_many_small_experts_whole_oracle():
+    _full_check(WORKLOADS["C3"])
 
 
 @pytest.mark.timeout(1100)
 def test_c4_large_shard():
-    _check_fullsize("C4", 6, ["lightest"])
+    import oracle as orc
+    from bf16_floor import ideal_bf16_layer, rb
+    from oracle.moe_expert_dense import expert_segment
+
+    w = WORKLOADS["C4"]
+    t0 = time.time()
+    say = lambda m: print(f"  [{time.time() - t0:6.1f} s] {m}", flush=True)
+    print(f"[fullsize] {w}", flush=True)
+    inputs = make_inputs(w)
+    say("inputs ready")
+    run = GpuRun(w, inputs).run()
+    assert run.status() == 0
+    ref_plan = check_plan_exact(run, inputs)
+    counts, offsets, perm, pos = ref_plan["counts"], ref_plan["offsets"], ref_plan["perm"], ref_plan["pos"]
+    say(f"routing exact; rows/expert max {counts.max()} median {int(np.median(counts))} min {counts.min()}")
+    p = oracle_problem(w, inputs)
+    wide = orc.bf16_bits_to_f64
+
+    # ---- 64 sampled tokens: outputs, gradients and the rows of every intermediate
+    toks = np.sort(np.random.default_rng(w.seed + 99).choice(w.N, size=64, replace=False)).astype(np.int32)
+    ref = orc.layer(p, tokens=toks, want_dw=False, want_internals=True)
+    sub = dict(inputs, X=inputs["X"][toks], dY=inputs["dY"][toks])
+    from paper_2103_13262_amd.synth import scaled
+    floor = ideal_bf16_layer(scaled(w, N=toks.size), sub, ref_plan["idx"][toks], ref_plan["w"][toks])
+    J = Judge(w.dtype, floor)
+    rows = pos.reshape(w.N, w.k)[toks].reshape(-1)          # expert-contiguous rows of the sample's assignments
+    for name, key in (("Z", "Z"), ("H", "H"), ("Ys", "O"), ("dYs", "dO"), ("dZ", "dZ"), ("dXs", "dXs")):
+        J.add(name, run.region(name)[rows], ref[key].reshape(rows.size, -1))
+    tl = toks.tolist()
+    J.add("Y", to_numpy64(run.Y[tl]), ref["Y"])
+    J.add("dX", to_numpy64(run.dX[tl]), ref["dX"])
+    dl_gpu = run.region("dl").reshape(w.N, w.k)
+    J.add("dl", dl_gpu[toks], ref["dl"])
+    say("sampled tokens compared")
+
+    # ---- weight gradients of the lightest, the median and the heaviest expert, over all rows routed to them
+    by_count = np.argsort(counts, kind="stable")
+    X64, dY64 = None, None
+    picks = {"lightest": int(by_count[0]), "median": int(by_count[len(by_count) // 2]), "heaviest": int(by_count[-1])}
+
+    def dense(e):
+        nonlocal X64, dY64
+        if X64 is None:
+            X64, dY64 = wide(inputs["X"]), wide(inputs["dY"])
+        a = perm[offsets[e]:offsets[e + 1]]              # the expert's assignments, ascending
+        return a, expert_segment(X64[a // w.k], wide(inputs["W1"][e]), wide(inputs["W2"][e]),
+                                 ref_plan["w"].reshape(-1)[a], dY64[a // w.k])
+
+    def ideal_dw(e):                                     # the ideal bf16 path's weight gradients of one expert
+        a, seg = dense(e)
+        H, Z, dYs = rb(seg["H"]), rb(seg["Z"]), rb(seg["dO"])
+        W2 = wide(inputs["W2"][e])
+        from bf16_floor import gelu_grad
+        dZ = rb((dYs @ W2.T) * gelu_grad(Z))
+        return rb(X64[a // w.k].T @ dZ), rb(H.T @ dYs)
+
+    for which, e in picks.items():
+        assert counts[e] > 0
+        if which == "heaviest":
+            _, seg = dense(e)
+            want1, want2 = seg["dW1"], seg["dW2"]
+        else:
+            toks_e = np.unique(perm[offsets[e]:offsets[e + 1]] // w.k).astype(np.int32)
+            r = orc.layer(p, tokens=toks_e, track=np.array([e], np.int32), only_tracked=True)
+            want1, want2 = r["dW1"][0], r["dW2"][0]
+            if which == "median":                        # the dense statement against the per-token oracle at this shape
+                _, seg = dense(e)
+                np.testing.assert_allclose(seg["dW1"], want1, rtol=1e-9, atol=1e-9 * float(np.abs(want1).max()))
+                np.testing.assert_allclose(seg["dW2"], want2, rtol=1e-9, atol=1e-9 * float(np.abs(want2).max()))
+        cache = {}
+        lazy = lambda i, e=e, cache=cache: (cache.setdefault("v", ideal_dw(e)))[i]
+        J.add("dW1", to_numpy64(run.dW1[e]), want1, floor_got=lambda: lazy(0), label=f"dW1[{which} e={e}, {counts[e]} rows]")
+        J.add("dW2", to_numpy64(run.dW2[e]), want2, floor_got=lambda: lazy(1), label=f"dW2[{which} e={e}, {counts[e]} rows]")
+        say(f"dW of expert {e} ({which}, {counts[e]} rows) compared")
+
+    # ---- gate gradient through properties that hold at any size
+    dWg, dbg = to_numpy64(run.dWg), to_numpy64(run.dbg)
+    flat_e = ref_plan["idx"].reshape(-1)
+    if X64 is None:
+        X64 = wide(inputs["X"])
+    expect = np.zeros((w.d, w.E))
+    for e in range(w.E):
+        a = np.nonzero(flat_e == e)[0]
+        expect[:, e] = X64[a // w.k].T @ dl_gpu.reshape(-1)[a]
+    J.add("dWg", dWg, expect, floor_got=lambda: rb(expect), label="dWg vs Xs^T dl(gpu)")
+    J.add("dbg", dbg, np.bincount(flat_e, weights=dl_gpu.reshape(-1), minlength=w.E), floor_got=None, label="dbg vs sum dl(gpu)")
+    scale = np.sqrt(np.mean(dWg * dWg))
+    assert np.max(np.abs(dWg.sum(1))) <= 0.05 * scale * np.sqrt(w.E)     # columns cancel over experts
+    J.check()
+    say("done")
