@@ -30,7 +30,8 @@
  * behind locks: the thread-local error string; per device, which kernels have had
  * their LDS limit raised and the device's compute-unit count (filled in on first
  * use); the event pool of the optional per-kernel timing (moe_profile_*: the one
- * place that creates HIP events).  All work is enqueued on `stream` (a hipStream_t
+ * place that creates HIP events); the 16 MiB device array of
+ * moe_scatter_backward_static.  All work is enqueued on `stream` (a hipStream_t
  * passed as void*, NULL = the null stream); no call synchronises with the host or
  * copies anything to the host, except moe_check_status and moe_profile_read, which
  * say so.  Calls return a status; nothing throws or aborts.
@@ -214,6 +215,26 @@ moe_status_t moe_gather_backward(const moe_desc_t *desc, const moe_plan_t *plan,
 moe_status_t moe_scatter_backward(const moe_desc_t *desc, const moe_plan_t *plan, const void *Wg, const void *Xs,
                                   const void *dXs, const float *dl, void *dX, void *dWg, float *dbg,
                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * moe_scatter_backward for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the workspace),
+ * same kernels and the same bits as moe_scatter_backward.  What that call keeps in the workspace (the table of
+ * 64-row pieces, the fp32 partial sums of the gate-matrix gradient by piece, the transposed gate matrix) lives
+ * in a device array of 16 MiB that is part of the library's code object: every GPU the library runs on holds
+ * its own copy until the process ends.  The call allocates and frees nothing (no hipMalloc, no hipFree, no
+ * allocating library routine); its first call on a device looks the array's address up.
+ *   Limit: (N k / 64 + E) (4 d + 4) + E d sizeof(dtype) + 16 (E + 1) bytes, each part rounded up to 256, must
+ *   fit in 16 MiB (all five benchmark workloads do); larger problems return MOE_ERR_WORKSPACE with the sizes in
+ *   moe_last_error() and must use moe_scatter_backward.
+ *   All calls on one GPU share that GPU's array, which keeps the last call's contents (nothing in it has to
+ *   start at zero: every word a kernel reads was written earlier in the same call).  Calls that overlap in time
+ *   on one GPU (different streams, different threads) race on it: the caller serialises them.
+ *   Unlike moe_scatter_backward it does not read the workspace that moe_plan wrote, only the plan arrays.
+ */
+moe_status_t moe_scatter_backward_static(const moe_desc_t *desc, const moe_plan_t *plan, const void *Wg, const void *Xs,
+                                         const void *dXs, const float *dl, void *dX, void *dWg, float *dbg,
+                                         void *stream);
 
 /*
  * Where a named intermediate lives inside the workspace (host-only; touches no device).

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe355.so")
 MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE, MOE_ERR_HIP = 0, -1, -2, -3, -4
 MOE_F32, MOE_BF16 = 0, 1
 EXPORTS = ("moe_workspace_bytes", "moe_workspace_region", "moe_check_status", "moe_plan", "moe_forward", "moe_backward",
-           "moe_bias_backward", "moe_balance_stats", "moe_scatter", "moe_gather", "moe_gather_backward", "moe_scatter_backward",
+           "moe_bias_backward", "moe_balance_stats", "moe_scatter", "moe_gather", "moe_gather_backward", "moe_scatter_backward", "moe_scatter_backward_static",
            "moe_last_error", "moe_profile_enable", "moe_profile_read")
 
 
@@ -70,6 +70,8 @@ def lib():
             getattr(L, name).restype = C.c_int
         L.moe_scatter_backward.argtypes = [C.POINTER(MoeDesc), C.POINTER(MoePlan)] + [vp] * 8 + [C.c_size_t, vp]
         L.moe_scatter_backward.restype = C.c_int
+        L.moe_scatter_backward_static.argtypes = [C.POINTER(MoeDesc), C.POINTER(MoePlan)] + [vp] * 8
+        L.moe_scatter_backward_static.restype = C.c_int
         L.moe_workspace_region.restype = C.c_int
         L.moe_workspace_region.argtypes = [C.POINTER(MoeDesc), C.c_char_p, C.POINTER(C.c_size_t),
                                            C.POINTER(C.c_size_t)]
@@ -183,6 +185,11 @@ def moe_scatter_backward(desc, plan, Wg, Xs, dXs, dl, dX, dWg, dbg, workspace, w
     _check(lib().moe_scatter_backward(C.byref(desc), None if plan is None else C.byref(plan), _p(Wg), _p(Xs), _p(dXs), _p(dl), _p(dX),
                                       _p(dWg), _p(dbg), _p(workspace), C.c_size_t(workspace_bytes),
                                       C.c_void_p(stream)))
+
+
+def moe_scatter_backward_static(desc, plan, Wg, Xs, dXs, dl, dX, dWg, dbg, stream=0):
+    _check(lib().moe_scatter_backward_static(C.byref(desc), None if plan is None else C.byref(plan), _p(Wg), _p(Xs), _p(dXs),
+                                             _p(dl), _p(dX), _p(dWg), _p(dbg), C.c_void_p(stream)))
 
 
 class MoeLayerBuffers:

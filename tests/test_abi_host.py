@@ -123,3 +123,22 @@ def test_null_misaligned_and_small_workspace_arguments():
         B.moe_bias_backward(d, plan, FAKE, FAKE, FAKE, ws - 1)
     assert ei.value.status == B.MOE_ERR_WORKSPACE
 
+
+def test_static_scratch_call_rejects_bad_arguments_and_what_does_not_fit():
+    """moe_scatter_backward_static: same checks as moe_scatter_backward, and a problem whose partial sums exceed the
+    fixed 16 MiB array is refused with the sizes in the message -- all before any device work."""
+    plan = B.make_plan(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    d = B.make_desc(16, 64, 64, 4, 2)
+    for c in (lambda: B.moe_scatter_backward_static(d, plan, FAKE, FAKE, FAKE, FAKE, FAKE, None, None),      # dWg NULL
+              lambda: B.moe_scatter_backward_static(d, plan, FAKE, FAKE + 2, FAKE, FAKE, FAKE, FAKE, None),  # Xs misaligned
+              lambda: B.moe_scatter_backward_static(d, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None)):     # plan NULL
+        with pytest.raises(B.MoeError) as ei:
+            c()
+        assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_scatter_backward_static(B.make_desc(16, 64, 64, 4, 2, score_all=1), plan, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None)
+    assert ei.value.status == B.MOE_ERR_UNSUPPORTED
+    big = B.make_desc(1 << 20, 4096, 32, 8, 2)     # (2^21 / 64 + 8) pieces x 4096 floats = 512 MiB of partial sums
+    with pytest.raises(B.MoeError) as ei:
+        B.moe_scatter_backward_static(big, plan, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None)
+    assert ei.value.status == B.MOE_ERR_WORKSPACE and "16777216" in str(ei.value)
