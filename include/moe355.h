@@ -123,9 +123,14 @@ moe_status_t moe_plan(const moe_desc_t *desc, const void *X, const void *Wg, con
  *   b1 device [E,h], b2 device [E,d] dtype, or NULL: the biases of the expert's two linear
  *   layers (the paper's expert is an FFN, Section 5.1): E_e(x) = GeLU(x W1[e] + b1[e]) W2[e] + b2[e].
  *   Y device [N,d] dtype, written.
- * Leaves Xs, Z (pre-activation), H and Ys in the workspace for moe_backward.  bf16: Z is the
+ * Leaves Z (pre-activation), H and Ys in the workspace for moe_backward.  bf16: Z is the
  * rounded accumulator, H = z * Phi(Z) with z the fp32 accumulator and Phi the normal CDF taken at
  * the stored Z (the erf GeLU up to that rounding inside Phi, which moves H by less than 6e-4).
+ * The two data movements of Section 4 are done on the fly where that saves a pass over memory: the
+ * first layer reads row perm[r] / k of X as row r of its input (no scattered copy is written in the
+ * forward pass; moe_backward writes Xs for the weight gradients), and with k = 1 and score_all = 0,
+ * where y is the one selected expert's output, the second layer writes its rows straight to their
+ * tokens' rows of Y (then no Ys is kept, and none is needed: the gate receives no gradient).
  */
 moe_status_t moe_forward(const moe_desc_t *desc, const moe_plan_t *plan, const void *X, const void *W1,
                          const void *W2, const void *b1, const void *b2, void *Y, void *workspace,
@@ -238,10 +243,10 @@ moe_status_t moe_scatter_backward_static(const moe_desc_t *desc, const moe_plan_
 
 /*
  * Where a named intermediate lives inside the workspace (host-only; touches no device).
- * Names: "Xs" [M,d] scattered inputs, "Z" [M,h] pre-activations, "H" [M,h] GeLU(Z), "Ys" [M,d]
- * expert outputs before the weighted gather (these four are valid after moe_forward);
- * "dYs" [M,d], "dZ" [M,h], "dXs" [M,d] (dtype elements) and "dl" [M] float, the gradient of the
- * selected logits (valid after moe_backward).  Rows are in expert-contiguous order (row r holds
+ * Names: "Z" [M,h] pre-activations, "H" [M,h] GeLU(Z), "Ys" [M,d]
+ * expert outputs before the weighted gather (valid after moe_forward; "Ys" not with k = 1 and
+ * score_all = 0); "Xs" [M,d] scattered inputs, "dYs" [M,d], "dZ" [M,h], "dXs" [M,d] (dtype elements)
+ * and "dl" [M] float, the gradient of the selected logits (valid after moe_backward).  Rows are in expert-contiguous order (row r holds
  * assignment perm[r]).  "status": the int32 that moe_check_status returns.  "clock": two int64 written by the last bf16 matrix-product launch,
  * shader cycles and ticks of the 100 MHz reference clock over the lifetime of one of its workgroups
  * (their ratio x 100 is the shader clock in MHz the launch ran at).  Returns MOE_ERR_INVALID_ARG for an

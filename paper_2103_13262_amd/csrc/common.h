@@ -193,6 +193,9 @@ struct GemmArgs {
     void* C2;         // kRowsNN_GeLU: GeLU output
     const void* Zin;  // kRowsNT_dGeLU: saved pre-activation [M,Nout]
     const void* bias; // kRowsNN_GeLU, kRowsNN: [E,Nout] added to the product (activation type), or NULL
+    const int32_t* a_gather;  // kRows*: row r of the A operand is A[a_gather[r] / a_gather_div, :] (the scatter done on the fly), or NULL
+    int a_gather_div;
+    const int32_t* c_scatter; // kRowsNN: row r of the product is written to C[c_scatter[r], :] (the gather done on the fly; top-1 only), or NULL
     int K;            // kRows*: reduction width;  kColsT: K1 (rows of C[e])
     int Nout;         // kRows*: columns of C;     kColsT: K2 (columns of C[e])
     long M;           // total rows (N*k)
@@ -210,6 +213,7 @@ struct GemmArgs {
     long long* clock_probe;    // [2]: shader cycles and 100 MHz ticks of workgroup 0 of the last launch
     const int32_t* skewed;     // 1: the experts' sizes are strongly skewed (decided by the plan step)
     int32_t* dyn_counters;     // [9]: next tile of every XCD's list and the number of workgroups that have finished; zero between launches
+    int whole_tiles;           // rows kinds: never cut a tile (another product in the same launch fills the idle workgroups)
     int on_demand;             // weight gradients: hand the tiles out from the counters whatever the sizes
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT

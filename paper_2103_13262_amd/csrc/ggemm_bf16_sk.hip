@@ -136,9 +136,10 @@ __device__ __forceinline__ int act_index(unsigned zb)   // zb: bf16 bit pattern 
 // reduction offset inside a block that the lane's chunk starts at (krow).
 //   !TRANS: src[row][k]; one load covers 64 / (BK/8) rows.
 //    TRANS: src[k][row]; CPR = R/8 chunks per k-row; lane p of load j covers k-row j*(64/CPR) + p/CPR.
+//   gather (!TRANS only): row r of the tile is the source's row gather[row0 + r] / div instead of row r.
 template <bool TRANS, int R, int NW, int L, int BK>
 __device__ __forceinline__ void setup_ptrs(const u16* base, long ld, int valid, int wave, int lane, const u16* (&ptr)[L],
-                                           int (&krow)[L])
+                                           int (&krow)[L], const int32_t* gather = nullptr, long row0 = 0, int div = 1)
 {
 #pragma unroll
     for (int i = 0; i < L; ++i) {
@@ -148,7 +149,8 @@ __device__ __forceinline__ void setup_ptrs(const u16* base, long ld, int valid, 
             int row = j * (64 / CK) + lane / CK;
             const int c = (lane % CK) ^ swz<BK>(row);
             row = row < valid ? row : valid - 1;
-            ptr[i] = base + (long)row * ld + c * 8;
+            const long src_row = gather ? (long)(gather[row0 + row] / div) : (long)row;
+            ptr[i] = base + src_row * ld + c * 8;
             krow[i] = c * 8;
         } else {
             constexpr int CPR = R / 8;
@@ -171,11 +173,13 @@ struct Item {
     int kb0, kb1;         // reduction blocks [kb0, kb1) of the tile
     int owner;            // the range holds the tile's last block: this workgroup writes the tile
     size_t b_off;         // rows kinds: expert * Nout + first column (where the tile's bias values start)
+    long row0;            // rows kinds: first row of the tile in the expert-contiguous order
 };
 
 struct Fin {              // what finishing an item needs once the streams have moved on to the next one
     size_t c_off, b_off;
     int Mt, Nt, owner;
+    long row0;
 };
 
 // CLS: 0 = all rows of every expert (tables counts / offsets / tileP); 1 = the rows in whole blocks of
@@ -286,7 +290,8 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         const int rows_per = BM / f, row_off = slice * rows_per;
         const long r0 = (long)offsets_[e] + (long)mt * BM + row_off;
         const int n0 = nt * BN;
-        it.A = (const u16*)g.A + r0 * g.K;  it.lda = g.K;
+        it.A = (const u16*)g.A + (g.a_gather ? 0 : r0 * g.K);  it.lda = g.K;   // (gathered rows: the base, see setup_ptrs)
+        it.row0 = r0;
         const u16* Be = (const u16*)g.B + (size_t)e * g.K * g.Nout;
         if constexpr (C::B_TRANS) { it.B = Be + n0; it.ldb = g.Nout; }
         else                      { it.B = Be + (size_t)n0 * g.K; it.ldb = g.K; }
@@ -295,7 +300,12 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         it.Mt = min(rows_per, counts_[e] - mt * BM - row_off);  it.Nt = min(BN, g.Nout - n0);  it.Kt = g.K;
     };
     if constexpr (KIND != kColsT) {
-        if (rem) {
+        if (rem && g.whole_tiles) {
+            // another product follows in this launch and takes up the workgroups that have nothing left to do here:
+            // the left-over tiles are computed whole, one per workgroup (no partial sums, no slices)
+            row_f = 1;
+            row_item = wj < rem;
+        } else if (rem) {
             constexpr int kMinSplitBlocks = kMinSplitDepth / BK;
             if (nkT >= 2 * kMinSplitBlocks) {
                 // long reductions: the left-over tiles' blocks, laid end to end, in equal contiguous ranges.  (Ranges
@@ -437,7 +447,10 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
     };
     // Point the streams at an item and request its first blocks (the ring must be free).
     auto start_item = [&](const Item& it) {
-        setup_ptrs<C::A_TRANS, BM, C::NW, C::LA, BK>(it.A, it.lda, it.Mt, wave, lane, pa, ka);
+        if constexpr (KIND != kColsT)
+            setup_ptrs<C::A_TRANS, BM, C::NW, C::LA, BK>(it.A, it.lda, it.Mt, wave, lane, pa, ka, g.a_gather, it.row0, g.a_gather_div);
+        else
+            setup_ptrs<C::A_TRANS, BM, C::NW, C::LA, BK>(it.A, it.lda, it.Mt, wave, lane, pa, ka);
         setup_ptrs<C::B_TRANS, BN, C::NW, C::LB, BK>(it.B, it.ldb, it.Nt, wave, lane, pb, kb);
         stepA = C::A_TRANS ? (long)BK * it.lda : BK;
         stepB = C::B_TRANS ? (long)BK * it.ldb : BK;
@@ -769,7 +782,11 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
                                 *Ch = pack8(x);
                             }
                         } else {
-                            *(uint4*)((u16*)g.C + o) = pack8(x);
+                            size_t oo = o;
+                            if constexpr (KIND == kRowsNN) {   // top-1: the row goes straight to its token's place in Y
+                                if (g.c_scatter) oo = (size_t)g.c_scatter[it.row0 + row] * ldc + (it.c_off - (size_t)it.row0 * ldc) + pcol;
+                            }
+                            *(uint4*)((u16*)g.C + oo) = pack8(x);
                         }
                     }
                     cur = nxt;
@@ -809,7 +826,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
             __builtin_amdgcn_s_waitcnt(0xc07f);
             __builtin_amdgcn_s_barrier();              // every wave is done reading the ring
         }
-        const Fin fin{cur.c_off, cur.b_off, cur.Mt, cur.Nt, cur.owner};
+        const Fin fin{cur.c_off, cur.b_off, cur.Mt, cur.Nt, cur.owner, cur.row0};
         if (cur.kb0 > 0) add_predecessor();   // the blocks before kb0 were summed by the workgroup just below
         have = next_item(cur);
         if (have) start_item(cur);
@@ -859,6 +876,17 @@ __device__ __forceinline__ void ggemm_classes(const GemmArgs& g, int ntn_big, in
     }
     const int W = gridDim.x >> 3;
     const long Tb = (long)g.cls[kClsPBig * (g.E + 1) + g.E] * ntn_big, Ts = (long)g.cls[kClsPSmall * (g.E + 1) + g.E] * ntn_small;
+    if (g.whole_tiles) {
+        // Followed by another product in the same launch: whole tiles only.  The big tiles go round the workgroups
+        // from the first on; the last pieces, in 128 x 256 tiles (a 128 x 512 tile of a deep reduction would be the
+        // longest item of the launch), start behind the big tiles' last round, so that no workgroup gets one of each.
+        ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big);
+        if (Ts == 0) return;
+        __syncthreads();
+        const int after = (int)(((Tb >> 3) + ((Tb & 7) ? 1 : 0)) % W);
+        ggemm_sk_body<KIND, 2, 4, 2, 2, 2, 64, 2>(g, 0, ntn_big, after < W - 1 ? after : 0, after < W - 1 ? W - after : W);
+        return;
+    }
     if (Ts == 0) { ggemm_sk_body<KIND, 2, 4, 4, 2, STAGES, BK, 1>(g, 0, ntn_big); return; }
     if (Tb == 0) { ggemm_sk_body<KIND, 1, 8, 4, 2, 3, 32, 2>(g, 0, ntn_small); return; }
     if (g.K >= 2 * kMinSplitDepth && W >= 2 && Tb < 8L * W) {
@@ -994,6 +1022,7 @@ void launch_pair_cfg(const GemmArgs& rows, const GemmArgs& cols, hipStream_t st)
     if (wgs < 8) return;
     GemmArgs r = rows, c = cols;
     c.on_demand = 1;
+    r.whole_tiles = 1;
     const int ntn1 = (r.Nout + C1::BN - 1) / C1::BN, ntn1s = (r.Nout + C1s::BN - 1) / C1s::BN;
     const int ntn2 = (c.Nout + C2::BN - 1) / C2::BN, ntm2 = (c.K + C2::BM - 1) / C2::BM;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(512), SMEM, st, r, ntn1, ntn1s, c, ntm2, ntn2);

@@ -15,13 +15,16 @@ struct TileF32 {
     const float* B; long sbk, sbn;   // B'(kk,n) = B[kk*sbk + n*sbn]
     float* C; float* C2; const float* Z; const float* bias; long ldc;   // bias: the expert's row at the tile's first column, or NULL
     int Mt, Nt, Kt;                  // valid extents of this tile / reduction length
+    const int32_t* gather; int div;  // rows kinds: row m of A' is A[gather[row0 + m] / div] (A then points at the base), or NULL
+    const int32_t* scatter;          // kRowsNN: row m of the tile is written to row scatter[row0 + m] of C (C then points at column n0 of the base), or NULL
+    long row0;
 };
 
 __global__ __launch_bounds__(256) void ggemm_f32_kernel(GemmArgs g, int ntn)
 {
     __shared__ float As[TK][TM + 4];
     __shared__ float Bs[TK][TN + 4];
-    TileF32 t;
+    TileF32 t{};
     const float* A = (const float*)g.A;
     const float* B = (const float*)g.B;
     if (g.kind == kColsT) {
@@ -46,11 +49,13 @@ __global__ __launch_bounds__(256) void ggemm_f32_kernel(GemmArgs g, int ntn)
         const int mt = tile - P[e];
         const long r0 = (long)g.offsets[e] + (long)mt * TM;
         const int n0 = nt * TN;
-        t.A = A + r0 * g.K; t.sam = g.K; t.sak = 1;
+        t.A = g.a_gather ? A : A + r0 * g.K; t.sam = g.K; t.sak = 1;
+        t.gather = g.a_gather; t.div = g.a_gather_div; t.row0 = r0;
+        t.scatter = g.kind == kRowsNN ? g.c_scatter : nullptr;
         const float* Be = B + (size_t)e * g.K * g.Nout;
         if (g.kind == kRowsNN || g.kind == kRowsNN_GeLU) { t.B = Be + n0; t.sbk = g.Nout; t.sbn = 1; }
         else { t.B = Be + (size_t)n0 * g.K; t.sbk = 1; t.sbn = g.K; }
-        t.C = (float*)g.C + r0 * g.Nout + n0;
+        t.C = (float*)g.C + (t.scatter ? 0 : r0 * g.Nout) + n0;
         t.C2 = g.C2 ? (float*)g.C2 + r0 * g.Nout + n0 : nullptr;
         t.Z = g.Zin ? (const float*)g.Zin + r0 * g.Nout + n0 : nullptr;
         t.bias = g.bias && (g.kind == kRowsNN || g.kind == kRowsNN_GeLU) ? (const float*)g.bias + (size_t)e * g.Nout + n0 : nullptr;
@@ -65,7 +70,12 @@ __global__ __launch_bounds__(256) void ggemm_f32_kernel(GemmArgs g, int ntn)
             const int kk = q / TM, m = q % TM;   // m fastest: for sam==1 (transposed A) reads coalesce
             const int kk2 = q % TK, m2 = q / TK; // kk fastest: for sak==1 reads coalesce
             const int K_ = t.sak == 1 ? kk2 : kk, M_ = t.sak == 1 ? m2 : m;
-            As[K_][M_] = (M_ < t.Mt && k0 + K_ < t.Kt) ? t.A[M_ * t.sam + (long)(k0 + K_) * t.sak] : 0.f;
+            float v = 0.f;
+            if (M_ < t.Mt && k0 + K_ < t.Kt) {
+                const long arow = t.gather ? (long)(t.gather[t.row0 + M_] / t.div) : (long)M_;
+                v = t.A[arow * t.sam + (long)(k0 + K_) * t.sak];
+            }
+            As[K_][M_] = v;
         }
         for (int q = threadIdx.x; q < TK * TN; q += 256) {
             const int kk = q / TN, n = q % TN;
@@ -96,7 +106,7 @@ __global__ __launch_bounds__(256) void ggemm_f32_kernel(GemmArgs g, int ntn)
         for (int j = 0; j < 4; ++j) {
             const int n = tx * 4 + j;
             if (n >= t.Nt) continue;
-            const size_t o = (size_t)m * t.ldc + n;
+            const size_t o = (size_t)(t.scatter ? t.scatter[t.row0 + m] : m) * t.ldc + n;
             float v = acc[i][j];
             if (t.bias) v += t.bias[n];
             switch (g.kind) {

@@ -157,6 +157,9 @@ static moe_status_t check_ws(const moe_desc_t* D, const void* ws, size_t bytes, 
     return MOE_OK;
 }
 
+// Top-1 with the score fixed at 1: moe_forward writes Y from the second layer and keeps no Ys.
+static bool direct_top1(const moe_desc_t& D) { return D.k == 1 && !D.score_all; }
+
 static void run_gemm(const moe_desc_t& D, GemmArgs& a, hipStream_t st)
 {
     if (D.dtype == MOE_BF16) launch_ggemm_bf16_sk(a, st);
@@ -300,9 +303,8 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     hipStream_t st = (hipStream_t)stream;
     char* ws = (char*)workspace;
 
-    { ScopedTimer tm(S_SCATTER, st); launch_scatter(D, X, plan->perm, ws + L.Xs, st); }
-    if ((s = check_launch("scatter")) != MOE_OK) return s;
-
+    // No scatter launch here: the first layer fetches row perm[r] / k of X as row r of its operand, which is the
+    // scatter of Section 4 done on the fly (moe_backward writes Xs when the weight gradient needs it).
     GemmArgs a{};
     a.M = (long)D.N * D.k;
     a.E = D.E;
@@ -314,14 +316,20 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     set_control(a, ws, L);
 
     a.kind = kRowsNN_GeLU;  // Z = Xs W1[e],  H = GeLU(Z)
-    a.A = ws + L.Xs; a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h; a.bias = b1;
+    a.A = X; a.a_gather = plan->perm; a.a_gather_div = D.k;
+    a.B = W1; a.C = ws + L.Z; a.C2 = ws + L.H; a.K = D.d; a.Nout = D.h; a.bias = b1;
     { ScopedTimer tm(S_FC1, st); run_gemm(D, a, st); }
     if ((s = check_launch("expert layer 1")) != MOE_OK) return s;
 
     a.kind = kRowsNN;       // Ys = H W2[e]
-    a.A = ws + L.H; a.B = W2; a.C = ws + L.Ys; a.C2 = nullptr; a.K = D.h; a.Nout = D.d; a.bias = b2;
+    a.A = ws + L.H; a.a_gather = nullptr; a.B = W2; a.C = ws + L.Ys; a.C2 = nullptr; a.K = D.h; a.Nout = D.d; a.bias = b2;
+    // Top-1 with the score fixed at 1 (softmax over one logit): y is the one expert's output, so the second layer
+    // writes row r straight to Y[perm[r]] - the gather of Section 4 done on the fly; Ys is not written.
+    const bool direct = direct_top1(D);
+    if (direct) { a.C = Y; a.c_scatter = plan->perm; }
     { ScopedTimer tm(S_FC2, st); run_gemm(D, a, st); }
     if ((s = check_launch("expert layer 2")) != MOE_OK) return s;
+    if (direct) return MOE_OK;
 
     { ScopedTimer tm(S_COMBINE, st); launch_combine(D, ws + L.Ys, plan->topk_w, plan->pos, Y, st); }
     return check_launch("combine");
@@ -354,8 +362,11 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     char* ws = (char*)workspace;
 
     if (D.N > 0) {
+        // Xs for the first layer's weight gradient and the gate's (the forward pass read X through perm instead)
+        { ScopedTimer tm(S_SCATTER, st); launch_scatter(D, X, plan->perm, ws + L.Xs, st); }
+        if ((s = check_launch("scatter")) != MOE_OK) return s;
         ScopedTimer tm(S_DCOMBINE, st);
-        launch_dcombine(D, dY, ws + L.Ys, plan->topk_w, plan->pos, ws + L.dYs, (float*)(ws + L.dl),
+        launch_dcombine(D, dY, direct_top1(D) ? nullptr : ws + L.Ys, plan->topk_w, plan->pos, ws + L.dYs, (float*)(ws + L.dl),
                         D.score_all ? (float*)(ws + L.gate_S) : nullptr, st);
         if ((s = check_launch("combine backward")) != MOE_OK) return s;
     }

@@ -82,6 +82,7 @@ __global__ __launch_bounds__(256) void combine_rows(const void* __restrict__ Ys,
 
 // ---- combine backward: one wavefront per token -------------------------------------------------
 //   dYs[pos[a],:] = w[a] * dY[t,:];  dw[a] = <dY[t,:], Ys[pos[a],:]>;  dl_j = w_j (dw_j - sum_i w_i dw_i)
+//   (Ys == NULL: the expert outputs were not kept - top-1 with the score fixed at 1, where dl is exactly zero)
 template <typename T>
 __global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY, const void* __restrict__ Ys,
                                                      const float* __restrict__ topk_w,
@@ -104,7 +105,11 @@ __global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY
         for (int c = lane; c < cpr; c += 64) {
             float g[V], y[V], o[V];
             Vec<T>::load(dY, (size_t)t * cpr + c, g);
-            Vec<T>::load(Ys, r * cpr + c, y);
+            if (Ys) Vec<T>::load(Ys, r * cpr + c, y);
+            else {                       // (top-1 with the score fixed at 1: dl is zero whatever the outputs were)
+#pragma unroll
+                for (int u = 0; u < V; ++u) y[u] = 0.f;
+            }
 #pragma unroll
             for (int u = 0; u < V; ++u) {
                 o[u] = w[j] * g[u];
