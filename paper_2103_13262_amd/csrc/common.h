@@ -165,7 +165,8 @@ void launch_scatter(const moe_desc_t& D, const void* X, const int32_t* perm, voi
 void launch_combine(const moe_desc_t& D, const void* Ys, const float* topk_w, const int32_t* pos, void* Y,
                     hipStream_t st);
 void launch_dcombine(const moe_desc_t& D, const void* dY, const void* Ys, const float* topk_w,
-                     const int32_t* pos, void* dYs, float* dl, float* S_out, hipStream_t st);
+                     const int32_t* pos, void* dYs, float* dl, float* S_out, const void* X, void* Xs, hipStream_t st);
+// (X, Xs: the scatter Xs[pos[a],:] = X[t,:] rides along, or NULL, NULL)
 void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, const void* dXs, const void* Wg,
                      const float* dl, const int32_t* topk_idx, const int32_t* pos, const int32_t* perm,
                      const int32_t* counts, const int32_t* offsets, void* dX, void* dWg, float* dbg, char* ws,

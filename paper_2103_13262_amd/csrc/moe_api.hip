@@ -362,12 +362,11 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
     char* ws = (char*)workspace;
 
     if (D.N > 0) {
-        // Xs for the first layer's weight gradient and the gate's (the forward pass read X through perm instead)
-        { ScopedTimer tm(S_SCATTER, st); launch_scatter(D, X, plan->perm, ws + L.Xs, st); }
-        if ((s = check_launch("scatter")) != MOE_OK) return s;
+        // The same launch writes Xs for the first layer's weight gradient and the gate's (the forward pass read X
+        // through perm instead).
         ScopedTimer tm(S_DCOMBINE, st);
         launch_dcombine(D, dY, direct_top1(D) ? nullptr : ws + L.Ys, plan->topk_w, plan->pos, ws + L.dYs, (float*)(ws + L.dl),
-                        D.score_all ? (float*)(ws + L.gate_S) : nullptr, st);
+                        D.score_all ? (float*)(ws + L.gate_S) : nullptr, X, ws + L.Xs, st);
         if ((s = check_launch("combine backward")) != MOE_OK) return s;
     }
 
@@ -506,7 +505,7 @@ moe_status_t moe_gather_backward(const moe_desc_t* desc, const moe_plan_t* plan,
     if (!dl || (reinterpret_cast<uintptr_t>(dl) & 3u)) { set_error("dl is NULL or not 4-byte aligned"); return MOE_ERR_INVALID_ARG; }
     if (desc->score_all) { set_error("moe_gather_backward / moe_scatter_backward carry the gradient of the selected experts only (score_all must be 0)"); return MOE_ERR_UNSUPPORTED; }
     if (desc->N == 0) return MOE_OK;
-    launch_dcombine(*desc, dY, Ys, plan->topk_w, plan->pos, dYs, dl, nullptr, (hipStream_t)stream);
+    launch_dcombine(*desc, dY, Ys, plan->topk_w, plan->pos, dYs, dl, nullptr, nullptr, nullptr, (hipStream_t)stream);
     return check_launch("gather backward");
 }
 

@@ -83,47 +83,59 @@ __global__ __launch_bounds__(256) void combine_rows(const void* __restrict__ Ys,
 // ---- combine backward: one wavefront per token -------------------------------------------------
 //   dYs[pos[a],:] = w[a] * dY[t,:];  dw[a] = <dY[t,:], Ys[pos[a],:]>;  dl_j = w_j (dw_j - sum_i w_i dw_i)
 //   (Ys == NULL: the expert outputs were not kept - top-1 with the score fixed at 1, where dl is exactly zero)
+//   Rides along (X != NULL): Xs[pos[a],:] = X[t,:], the scatter that the weight gradients of the first layer and of
+//   the gate read; the token's row is in hand anyway, and the backward pass saves a launch.
 template <typename T>
 __global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY, const void* __restrict__ Ys,
                                                      const float* __restrict__ topk_w,
                                                      const int32_t* __restrict__ pos, void* __restrict__ dYs,
                                                      float* __restrict__ dl, long N, int k, int cpr,
-                                                     float* __restrict__ S_out)   // S_out: sum_i w_i dw_i per token, or NULL
+                                                     float* __restrict__ S_out,   // S_out: sum_i w_i dw_i per token, or NULL
+                                                     const uint4* __restrict__ X, uint4* __restrict__ Xs)
 {
     constexpr int V = Vec<T>::N;
     const int lane = threadIdx.x & 63;
     const long t = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= N) return;
     float w[kMaxK], dw[kMaxK];
+    size_t r[kMaxK];
 #pragma unroll
     for (int j = 0; j < kMaxK; ++j) {
-        if (j >= k) break;
-        const long a = t * k + j;
-        const size_t r = (size_t)pos[a];
-        w[j] = topk_w[a];
-        float part = 0.f;
-        for (int c = lane; c < cpr; c += 64) {
-            float g[V], y[V], o[V];
-            Vec<T>::load(dY, (size_t)t * cpr + c, g);
-            if (Ys) Vec<T>::load(Ys, r * cpr + c, y);
-            else {                       // (top-1 with the score fixed at 1: dl is zero whatever the outputs were)
+        dw[j] = 0.f;
+        if (j < k) { r[j] = (size_t)pos[t * k + j]; w[j] = topk_w[t * k + j]; }
+    }
+    for (int c = lane; c < cpr; c += 64) {
+        float g[V];
+        Vec<T>::load(dY, (size_t)t * cpr + c, g);
+        uint4 x = make_uint4(0, 0, 0, 0);
+        if (X) x = X[(size_t)t * cpr + c];
+#pragma unroll
+        for (int j = 0; j < kMaxK; ++j) {
+            if (j >= k) break;
+            float y[V], o[V];
+            if (Ys) Vec<T>::load(Ys, r[j] * cpr + c, y);
+            else {
 #pragma unroll
                 for (int u = 0; u < V; ++u) y[u] = 0.f;
             }
 #pragma unroll
             for (int u = 0; u < V; ++u) {
                 o[u] = w[j] * g[u];
-                part = fmaf(g[u], y[u], part);
+                dw[j] = fmaf(g[u], y[u], dw[j]);
             }
-            Vec<T>::store(dYs, r * cpr + c, o);
+            Vec<T>::store(dYs, r[j] * cpr + c, o);
+            if (X) Xs[r[j] * cpr + c] = x;
         }
-        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
-        dw[j] = part;
     }
     float s = 0.f;
 #pragma unroll
-    for (int j = 0; j < kMaxK; ++j)
-        if (j < k) s = fmaf(w[j], dw[j], s);
+    for (int j = 0; j < kMaxK; ++j) {
+        if (j >= k) break;
+        float part = dw[j];
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+        dw[j] = part;
+        s = fmaf(w[j], part, s);
+    }
     if (lane == 0) {
 #pragma unroll
         for (int j = 0; j < kMaxK; ++j)
@@ -134,14 +146,14 @@ __global__ __launch_bounds__(256) void dcombine_rows(const void* __restrict__ dY
 
 // ---- dX[t,:] = sum_j dXs[pos[a],:] + sum_j dl[a] * Wg[:, idx[a]] ------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void gate_bwd_dx(const void* __restrict__ dXs, const void* __restrict__ WgT,
-                                                   const float* __restrict__ dl, const int32_t* __restrict__ topk_idx,
-                                                   const int32_t* __restrict__ pos, void* __restrict__ dX, long N, int k,
-                                                   int cpr, const float* __restrict__ dxd)   // dxd: [N][d] float to add, or NULL
+__device__ __forceinline__ void gate_bwd_dx_body(long block, long blocks, const void* __restrict__ dXs, const void* __restrict__ WgT,
+                                                 const float* __restrict__ dl, const int32_t* __restrict__ topk_idx,
+                                                 const int32_t* __restrict__ pos, void* __restrict__ dX, long N, int k,
+                                                 int cpr, const float* __restrict__ dxd)   // dxd: [N][d] float to add, or NULL
 {
     constexpr int V = Vec<T>::N;
     const long total = N * cpr;
-    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+    for (long i = block * 256 + threadIdx.x; i < total; i += blocks * 256) {
         const long t = i / cpr;
         const int c = (int)(i - t * cpr);
         float acc[V];
@@ -254,13 +266,13 @@ __global__ __launch_bounds__(512) void dwg_partial(const void* __restrict__ Xs, 
 // grid (ceil(d / 256), E): a thread owns one row of one expert's column, so that the threads of a wavefront read
 // consecutive floats of every piece; the pieces are added in ascending order (loads four at a time, sums in order).
 template <typename G>
-__global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part, const float* __restrict__ bpart,
-                                                 const int32_t* __restrict__ P64, G* __restrict__ dWg,
-                                                 float* __restrict__ dbg, int d, int E, int accumulate,
-                                                 const float* __restrict__ dense_part,     // [nch][E][d] to add, or NULL
-                                                 const float* __restrict__ dense_bpart, int nch)
+__device__ __forceinline__ void dwg_final_body(int bx, int e, const float* __restrict__ part, const float* __restrict__ bpart,
+                                               const int32_t* __restrict__ P64, G* __restrict__ dWg,
+                                               float* __restrict__ dbg, int d, int E, int accumulate,
+                                               const float* __restrict__ dense_part,     // [nch][E][d] to add, or NULL
+                                               const float* __restrict__ dense_bpart, int nch)
 {
-    const int row = blockIdx.x * 256 + threadIdx.x, e = blockIdx.y;
+    const int row = bx * 256 + threadIdx.x;
     const int q1 = P64[e + 1];
     if (row < d) {
         float s = 0.f;
@@ -290,6 +302,26 @@ __global__ __launch_bounds__(256) void dwg_final(const float* __restrict__ part,
         if (accumulate) s += dbg[e];
         dbg[e] = s;
     }
+}
+
+// The two kernels that follow the partial sums of the gate-matrix gradient, in one launch: the first fgx * E
+// workgroups add every expert's pieces (dWg, dbg), the others write dX.  Neither reads what the other writes.
+template <typename T, typename G>
+__global__ __launch_bounds__(256) void gate_bwd_tail(int fgx, const float* __restrict__ part, const float* __restrict__ bpart,
+                                                     const int32_t* __restrict__ P64, G* __restrict__ dWg, float* __restrict__ dbg,
+                                                     int d, int E, int accumulate, const float* __restrict__ dense_part,
+                                                     const float* __restrict__ dense_bpart, int nch,
+                                                     const void* __restrict__ dXs, const void* __restrict__ WgT,
+                                                     const float* __restrict__ dl, const int32_t* __restrict__ topk_idx,
+                                                     const int32_t* __restrict__ pos, void* __restrict__ dX, long N, int k, int cpr,
+                                                     const float* __restrict__ dxd)
+{
+    const int nfinal = fgx * E;
+    if ((int)blockIdx.x < nfinal)
+        dwg_final_body<G>((int)blockIdx.x % fgx, (int)blockIdx.x / fgx, part, bpart, P64, dWg, dbg, d, E, accumulate, dense_part,
+                          dense_bpart, nch);
+    else
+        gate_bwd_dx_body<T>((long)blockIdx.x - nfinal, (long)gridDim.x - nfinal, dXs, WgT, dl, topk_idx, pos, dX, N, k, cpr, dxd);
 }
 
 // out[e][c] = sum of the pieces of expert e, in ascending order (the column sums of its segment).
@@ -333,16 +365,16 @@ void launch_combine(const moe_desc_t& D, const void* Ys, const float* topk_w, co
 }
 
 void launch_dcombine(const moe_desc_t& D, const void* dY, const void* Ys, const float* topk_w,
-                     const int32_t* pos, void* dYs, float* dl, float* S_out, hipStream_t st)
+                     const int32_t* pos, void* dYs, float* dl, float* S_out, const void* X, void* Xs, hipStream_t st)
 {
     const int cpr = (int)((size_t)D.d * dtype_size(D.dtype) / 16);
     const unsigned g = (unsigned)((D.N + 3) / 4);
     if (D.dtype == MOE_BF16)
         hipLaunchKernelGGL(dcombine_rows<unsigned short>, dim3(g), dim3(256), 0, st, dY, Ys, topk_w, pos, dYs, dl,
-                           (long)D.N, D.k, cpr, S_out);
+                           (long)D.N, D.k, cpr, S_out, (const uint4*)X, (uint4*)Xs);
     else
         hipLaunchKernelGGL(dcombine_rows<float>, dim3(g), dim3(256), 0, st, dY, Ys, topk_w, pos, dYs, dl, (long)D.N,
-                           D.k, cpr, S_out);
+                           D.k, cpr, S_out, (const uint4*)X, (uint4*)Xs);
 }
 
 void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, const void* dXs, const void* Wg,
@@ -365,29 +397,29 @@ void launch_gate_bwd(const moe_desc_t& D, const WsLayout& L, const void* Xs, con
     float* bpart = (float*)(ws + L.dbg_part);
     const int32_t* P64 = (const int32_t*)(ws + L.tileP) + tile_height_index(64) * (D.E + 1);
     const dim3 pg((unsigned)L.dwg_pieces, (cpr + 63) / 64);
-    const dim3 fg((unsigned)((D.d + 255) / 256), (unsigned)D.E);
     const unsigned xg = grid_for((long)D.N * cpr);
     void* WgT = ws + L.WgT;
+    const int fgx = (D.d + 255) / 256;
+    const dim3 tg((unsigned)(fgx * D.E) + xg);
     if (D.dtype == MOE_BF16) {
         using T = unsigned short;
         hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr,
                            (const T*)Wg, (T*)WgT);
         if (D.grad_dtype == MOE_BF16)
-            hipLaunchKernelGGL(dwg_final<unsigned short>, fg, dim3(256), 0, st, (const float*)part,
-                               (const float*)bpart, P64, (unsigned short*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch);
+            hipLaunchKernelGGL((gate_bwd_tail<T, unsigned short>), tg, dim3(256), 0, st, fgx, (const float*)part, (const float*)bpart, P64,
+                               (unsigned short*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch, dXs, (const void*)WgT, dl,
+                               topk_idx, pos, dX, (long)D.N, D.k, cpr, dxd);
         else
-            hipLaunchKernelGGL(dwg_final<float>, fg, dim3(256), 0, st, (const float*)part, (const float*)bpart,
-                               P64, (float*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch);
-        hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
-                           (long)D.N, D.k, cpr, dxd);
+            hipLaunchKernelGGL((gate_bwd_tail<T, float>), tg, dim3(256), 0, st, fgx, (const float*)part, (const float*)bpart, P64,
+                               (float*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch, dXs, (const void*)WgT, dl, topk_idx,
+                               pos, dX, (long)D.N, D.k, cpr, dxd);
     } else {
         using T = float;
         hipLaunchKernelGGL(dwg_partial<T>, pg, dim3(512), 0, st, Xs, dl, perm, counts, offsets, P64, part, bpart, D.E, D.d, cpr,
                            (const T*)Wg, (T*)WgT);
-        hipLaunchKernelGGL(dwg_final<float>, fg, dim3(256), 0, st, (const float*)part, (const float*)bpart,
-                           P64, (float*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch);
-        hipLaunchKernelGGL(gate_bwd_dx<T>, dim3(xg), dim3(256), 0, st, dXs, (const void*)WgT, dl, topk_idx, pos, dX,
-                           (long)D.N, D.k, cpr, dxd);
+        hipLaunchKernelGGL((gate_bwd_tail<T, float>), tg, dim3(256), 0, st, fgx, (const float*)part, (const float*)bpart, P64,
+                           (float*)dWg, dbg, D.d, D.E, D.accumulate, dpart, dbpart, nch, dXs, (const void*)WgT, dl, topk_idx, pos,
+                           dX, (long)D.N, D.k, cpr, dxd);
     }
 }
 
