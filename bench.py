@@ -39,6 +39,11 @@ def parse():
                     help="throughput of the grouped matrix products against the batch an expert sees (the paper's "
                          "Section 4 figure of GeMM throughput against problem size): token counts at d_m=1024, "
                          "d_h=4096, 16 experts, k=2, i.e. N/8 rows per expert; one JSON line per count")
+    ap.add_argument("--calibrate-hbm-counters", type=int, default=0, metavar="MiB",
+                    help="no benchmark: a plain device copy of this many MiB, five times, for scaling rocprofv3's FETCH_SIZE / "
+                         "WRITE_SIZE (run under `rocprofv3 --pmc FETCH_SIZE`, then WRITE_SIZE: the copy kernel moves exactly that "
+                         "many MiB in and out per launch, so counter / (MiB * 1024) is the factor by which the counter over- or "
+                         "under-reports KiB on this machine; use a size above the 256 MB Infinity Cache, e.g. 1024)")
     ap.add_argument("--library-gemm", action="store_true",
                     help="context only: the rate of the vendor library's dense bf16 product (torch.matmul) on the six "
                          "product shapes of the workload with equal experts, i.e. what a tuned plain GEMM reaches on "
@@ -63,11 +68,21 @@ def cpu_baseline(w, inputs, n_tokens):
                       f"weight gradients, {dt:.1f} s"}
 
 
-# HBM bytes per grouped-GEMM launch (mean of the four launches of a step, which hold six products), from two rocprofv3 --pmc runs of this
-# file (FETCH_SIZE, then WRITE_SIZE), each divided by what the same counter reads for a plain 1 GiB copy
-# (0.500 and 1.000 of the true KiB); profiles/C1_hbm_traffic_pmc.md holds the commands and per-kernel figures.
-# Counters cannot be read from inside a run, so this is the stored measurement, not a live one.
-MEASURED_HBM_BYTES_PER_GEMM_LAUNCH = {"C1": 568.6e6}
+def measured_hbm_bytes_per_gemm_launch(workload):
+    """HBM bytes per grouped-GEMM launch (mean over the launches of a step), from the tracked summary of two
+    rocprofv3 --pmc runs of this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for a
+    plain 1 GiB copy: profiles/<workload>_hbm_traffic_pmc.md holds the commands, the per-kernel figures and the line
+    `grouped_gemm_hbm_bytes_per_launch = <bytes>` that is read here.  Counters cannot be read from inside a run, so
+    this is the stored measurement, not a live one; None if there is no summary for the workload."""
+    import os
+    import re
+
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{workload}_hbm_traffic_pmc.md")
+    try:
+        m = re.search(r"^grouped_gemm_hbm_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
+    except OSError:
+        return None
+    return float(m.group(1)) if m else None
 
 
 def main():
@@ -84,13 +99,21 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if a.calibrate_hbm_counters:
+        src = torch.empty(a.calibrate_hbm_counters << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration_copy_mib": a.calibrate_hbm_counters, "launches": 5}))
+        return
     B.lib()   # raises if the HIP library has not been built: there is no fallback
     if a.sweep_experts:
         for E in (int(v) for v in a.sweep_experts.split(",")):
             a.custom, a.cpu_sample_tokens = f"4096,1024,4096,{E},2", 0
             out = run(a, torch, B, WORKLOADS, make_inputs)
             kt = {n: v["avg_us"] * v["launches_per_step"] for n, v in out["kernels"].items()}
-            fwd = sum(kt.get(n, 0.0) for n in ("scatter", "ggemm_fc1_gelu", "ggemm_fc2", "combine"))
+            fwd = sum(kt.get(n, 0.0) for n in ("ggemm_fc1_gelu", "ggemm_fc2", "combine"))
             plan = sum(kt.get(n, 0.0) for n in ("gate_topk", "plan"))
             print(json.dumps({"sweep": "experts", "n_b": 4096, "d_m": 1024, "d_h": 4096, "k": 2, "n_e": E,
                               "ms_per_step": out["ms_per_step"], "gate_and_plan_ms": plan / 1e3, "forward_ms": fwd / 1e3,
@@ -194,7 +217,8 @@ def run(a, torch, B, WORKLOADS, make_inputs):
     # the data-movement kernels against the HBM roofline: algorithmic bytes per launch / mean duration
     eb = 2 if bf else 4
     Md, Nd = w.M * w.d * eb, w.N * w.d * eb
-    moved = {"gate_topk": Nd, "scatter": 2 * Md, "combine": Md + Nd, "dcombine": Nd + 2 * Md, "gate_bwd": 2 * Md + 2 * Nd}
+    # (the combine backward also writes the scattered inputs Xs: it reads X, dY and Ys and writes Xs and dYs)
+    moved = {"gate_topk": Nd, "combine": Md + Nd, "dcombine": 2 * Nd + (0 if w.k == 1 else Md) + 2 * Md, "gate_bwd": 2 * Md + 2 * Nd}
     for n, nbytes in moved.items():
         if n in prof and prof[n][0]:
             c, t = prof[n]
@@ -211,7 +235,7 @@ def run(a, torch, B, WORKLOADS, make_inputs):
                 "kernel": ("ggemm_cls_kernel / ggemm_pair_kernel / ggemm_sk_kernel" if bf else "ggemm_f32_kernel")
                 + " (%d launches of 6 products per step)" % round(g_launches / a.steps),
                 "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                "traffic": MEASURED_HBM_BYTES_PER_GEMM_LAUNCH.get(w.name) if not a.custom else None,
+                "traffic": measured_hbm_bytes_per_gemm_launch(w.name) if not a.custom else None,
                 "flops_per_launch": flops_launch, "avg_launch_us": avg_launch_ms * 1e3,
                 # context: the same fraction against 256 CUs x 4096 flop/clk at the clock measured during the launch
                 "shader_clock_mhz": clock_mhz,
