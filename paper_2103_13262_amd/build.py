@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe355.so")
-SOURCES = ["moe_api.hip", "gate_topk.hip", "gate_dense.hip", "plan.hip", "rowmove.hip", "noalloc.hip", "ggemm_f32.hip", "ggemm_bf16_sk.hip"]
+SOURCES = ["moe_api.hip", "gate_topk.hip", "gate_bf16.hip", "gate_dense.hip", "plan.hip", "rowmove.hip", "noalloc.hip", "ggemm_f32.hip", "ggemm_bf16_sk.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall",

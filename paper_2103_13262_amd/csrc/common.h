@@ -51,6 +51,7 @@ struct WsLayout {
     size_t dense_part;   // [ceil(N/512)][E][d] float: their contribution to dWg, by chunk of 512 tokens
     size_t dense_bpart;  // [ceil(N/512)][E] float: and to dbg
     int dense_chunks;
+    size_t gate_fail; // [1 + N] int32: how many tokens the fast gate kernel could not certify, then their ids
     size_t WgT;       // [E][d] gate matrix transposed (written by the plan step for E > 32 and by the backward pass), element type = desc.dtype
     size_t zeros;     // the control block (see Ctl below): 1 KB of zeros, source of masked reduction rows, then the control words
     size_t sk_flags;  // [kSkPhases][kMaxPersistentWgs] int32 "partial sum ready", zeroed with the zero page
@@ -105,6 +106,7 @@ inline WsLayout ws_layout(const moe_desc_t& D)
     L.dwg_part = take((size_t)L.dwg_pieces * D.d * sizeof(float));
     L.dbg_part = take((size_t)L.dwg_pieces * sizeof(float));
     L.bias_part = take((size_t)L.dwg_pieces * (D.d > D.h ? D.d : D.h) * sizeof(float));
+    L.gate_fail = take(((size_t)D.N + 1) * sizeof(int32_t));
     L.WgT = take((size_t)D.E * D.d * b);
     L.dense_chunks = (D.N + 511) / 512;
     if (D.score_all || D.balance_stats) {
@@ -156,7 +158,11 @@ template <typename Kern> static bool allow_dynamic_lds(Kern kern, int bytes)
 
 // ---- kernel launchers (each enqueues on `st`; operand shapes are validated by the callers) ----
 void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
-                      float* topk_w, void* WgT, double* logits, double* lse, hipStream_t st);
+                      float* topk_w, void* WgT, double* logits, double* lse, int32_t* gate_fail, hipStream_t st);
+// bf16 with 33 to 256 experts and no caller of the stored logits: fp32 logits on the bf16 matrix cores with a certified
+// margin, fp64 for the k selected logits and for the tokens that cannot be certified (gate_fail: [1 + N] int32 scratch)
+void launch_gate_bf16(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx, float* topk_w,
+                      void* WgT, int32_t* gate_fail, hipStream_t st);
 // (WgT: [E][d] scratch for the transposed gate matrix; logits [N][E] and lse [N]: only with desc.score_all, else NULL)
 void launch_plan(const moe_desc_t& D, const WsLayout& L, const int32_t* topk_idx, int32_t* counts,
                  int32_t* offsets, int32_t* pos, int32_t* perm, char* ws, hipStream_t st);

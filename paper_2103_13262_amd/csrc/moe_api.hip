@@ -228,6 +228,7 @@ moe_status_t moe_workspace_region(const moe_desc_t* desc, const char* name, size
         {"Xs", L.Xs, M * desc->d * b}, {"Z", L.Z, M * desc->h * b},     {"H", L.H, M * desc->h * b},
         {"Ys", L.Ys, M * desc->d * b}, {"dYs", L.dYs, M * desc->d * b}, {"dZ", L.dZ, M * desc->h * b},
         {"dXs", L.dXs, M * desc->d * b}, {"dl", L.dl, M * sizeof(float)},
+        {"gate_uncertified", L.gate_fail, ((size_t)desc->N + 1) * sizeof(int32_t)},
         {"status", L.sk_error, sizeof(int32_t)},
         {"clock", L.zeros + kCtlClock * sizeof(int32_t), 2 * sizeof(long long)},
     };
@@ -271,7 +272,8 @@ moe_status_t moe_plan(const moe_desc_t* desc, const void* X, const void* Wg, con
         ScopedTimer tm(S_GATE, st);
         launch_gate_topk(D, X, Wg, bg, plan->topk_idx, plan->topk_w, (char*)workspace + L.WgT,
                          (D.score_all || D.balance_stats) ? (double*)((char*)workspace + L.logits) : nullptr,
-                         (D.score_all || D.balance_stats) ? (double*)((char*)workspace + L.lse) : nullptr, st);
+                         (D.score_all || D.balance_stats) ? (double*)((char*)workspace + L.lse) : nullptr,
+                         (int32_t*)((char*)workspace + L.gate_fail), st);
         if ((s = check_launch("gate/top-k")) != MOE_OK) return s;
     }
     // With N == 0 the plan kernels still run: they write counts = 0, offsets = 0 and empty tile tables.

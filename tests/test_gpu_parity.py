@@ -167,6 +167,31 @@ def test_engineered_ties_resolve_to_lowest_expert():
     check_plan_exact(rb, ib)
 
 
+def test_engineered_ties_with_many_experts_take_the_exact_path():
+    """More than 32 experts in bf16: the gate ranks fp32 logits from the matrix cores and certifies the margin; equal
+    gate columns, an all-zero token and small-integer inputs (many exact ties) must all fall to the exact fp64 path and
+    resolve to the lower expert id, bit for bit as the oracle."""
+    from paper_2103_13262_amd.synth import f32_to_bf16_bits
+
+    g = np.random.default_rng(5)
+    for E, k in ((40, 3), (200, 8)):
+        w = Workload("ties_wide_bf16", 300, 64, 32, E, k, "bf16", 0.0, 0)
+        inputs = make_inputs(w)
+        X = g.integers(-3, 4, (w.N, w.d)).astype(np.float32)
+        Wg = g.integers(-2, 3, (w.d, w.E)).astype(np.float32)
+        Wg[:, 7] = Wg[:, 2]
+        Wg[:, 39] = Wg[:, 0]
+        Wg[:, 33] = Wg[:, 34]
+        X[5] = 0
+        inputs.update(X=f32_to_bf16_bits(X), Wg=f32_to_bf16_bits(Wg))
+        run = GpuRun(w, inputs)
+        run.plan()
+        run.torch.cuda.synchronize()
+        run.check_guards()
+        ref = check_plan_exact(run, inputs)
+        assert ref["idx"][5].tolist() == list(range(k))
+
+
 def test_structure_invariants_and_roundtrip():
     w = Workload("inv", 700, 64, 96, 10, 2, "bf16", 0.8, 31)
     inputs = make_inputs(w)
