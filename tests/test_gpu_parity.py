@@ -168,28 +168,39 @@ def test_engineered_ties_resolve_to_lowest_expert():
 
 
 def test_engineered_ties_with_many_experts_take_the_exact_path():
-    """More than 32 experts in bf16: the gate ranks fp32 logits from the matrix cores and certifies the margin; equal
-    gate columns, an all-zero token and small-integer inputs (many exact ties) must all fall to the exact fp64 path and
-    resolve to the lower expert id, bit for bit as the oracle."""
+    """33 to 256 experts in bf16: the gate ranks fp32 logits from the matrix cores and keeps as candidates whatever its
+    error bound cannot separate from the k-th largest.  Equal gate columns and small-integer inputs (many exact ties)
+    must resolve to the lower expert id; two columns that differ in one small element (logits a few 1e-3 apart at
+    magnitude 10: inside the bound for some tokens, outside for others) must be ranked as in exact arithmetic; all-zero
+    tokens (every logit equal: more candidates than the first kernel takes) must reach the all-fp64 second kernel, more
+    of them than that kernel has wavefronts.  Everything bit for bit as the oracle."""
     from paper_2103_13262_amd.synth import f32_to_bf16_bits
 
     g = np.random.default_rng(5)
-    for E, k in ((40, 3), (200, 8)):
-        w = Workload("ties_wide_bf16", 300, 64, 32, E, k, "bf16", 0.0, 0)
+    for E, k, N, zero_rows in ((40, 3, 300, [5]), (100, 2, 3000, list(range(1000, 2600))), (200, 8, 300, [5])):
+        w = Workload("ties_wide_bf16", N, 64, 32, E, k, "bf16", 0.0, 0)
         inputs = make_inputs(w)
         X = g.integers(-3, 4, (w.N, w.d)).astype(np.float32)
         Wg = g.integers(-2, 3, (w.d, w.E)).astype(np.float32)
         Wg[:, 7] = Wg[:, 2]
         Wg[:, 39] = Wg[:, 0]
         Wg[:, 33] = Wg[:, 34]
-        X[5] = 0
+        Wg[:, 21] = 3 * Wg[:, 20]                # two columns that win often ...
+        Wg[11, 21] = 0
+        Wg[:, 22] = Wg[:, 21]
+        Wg[11, 22] = 2.0 ** -9                   # ... and differ in one small element
+        X[zero_rows] = 0
         inputs.update(X=f32_to_bf16_bits(X), Wg=f32_to_bf16_bits(Wg))
         run = GpuRun(w, inputs)
         run.plan()
         run.torch.cuda.synchronize()
         run.check_guards()
         ref = check_plan_exact(run, inputs)
-        assert ref["idx"][5].tolist() == list(range(k))
+        assert ref["idx"][zero_rows[0]].tolist() == list(range(k))
+        assert np.any(ref["idx"] == 21) and np.any(ref["idx"] == 22)
+        off, n = B.moe_workspace_region(run.desc, "gate_uncertified")
+        listed = run.workspace[off:off + n].view(run.torch.int32).cpu().numpy()
+        assert listed[0] >= len(zero_rows) and set(zero_rows) <= set(listed[1:1 + listed[0]].tolist())
 
 
 def test_structure_invariants_and_roundtrip():
