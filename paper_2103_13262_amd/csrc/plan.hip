@@ -31,26 +31,41 @@ __global__ __launch_bounds__(256) void plan_hist(const int32_t* __restrict__ idx
     for (int e = threadIdx.x; e < E; e += 256) hist[(size_t)blockIdx.x * E + e] = sh[e];
 }
 
-// Exclusive scan of one int per thread over a 1024-thread workgroup. `total` receives the sum.
-__device__ __forceinline__ int block_excl_scan_1024(int v, int* s_wave /*[16]*/, int* total)
+// Exclusive scans of NV ints per thread over a 1024-thread workgroup, all at once (v[i] -> sum of v[i] over the
+// threads below); `total[i]` receives the sums.  Threads n_used and above hold zeros: their wavefronts skip the
+// shuffles (the LDS crossbar that carries them is shared by all sixteen).
+template <int NV>
+__device__ __forceinline__ void block_excl_scan_1024(int (&v)[NV], int (*s_wave)[NV] /*[16][NV]*/, int (&total)[NV], int n_used)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = v;
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(inc, off, 64);
-        if (lane >= off) inc += o;
+    int inc[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) inc[i] = v[i];
+    if (wave * 64 < n_used) {
+        for (int off = 1; off < 64; off <<= 1) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int o = __shfl_up(inc[i], off, 64);
+                if (lane >= off) inc[i] += o;
+            }
+        }
     }
-    __syncthreads();  // s_wave may still be read by a previous call
-    if (lane == 63) s_wave[wave] = inc;
+    if (lane == 63) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) s_wave[wave][i] = inc[i];
+    }
     __syncthreads();
-    int wbase = 0, tot = 0;
-    for (int w = 0; w < 16; ++w) {
-        const int c = s_wave[w];
-        if (w < wave) wbase += c;
-        tot += c;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        int wbase = 0, tot = 0;
+        for (int w = 0; w * 64 < n_used; ++w) {
+            const int c = s_wave[w][i];
+            if (w < wave) wbase += c;
+            tot += c;
+        }
+        total[i] = tot;
+        v[i] = wbase + inc[i] - v[i];
     }
-    *total = tot;
-    return wbase + inc - v;
 }
 
 constexpr int kFusedHistInts = 8192;   // chunk histograms that plan_scan builds itself when they fit (32 KB of LDS)
@@ -65,8 +80,8 @@ __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ id
 {
     // the control block: the page read in place of masked rows and the control words of the grouped products
     if (threadIdx.x < kCtlWords) zeros[threadIdx.x] = 0;
-    __shared__ int s_cnt[kMaxE];
-    __shared__ int s_wave[16];
+    __shared__ __align__(16) int s_cnt[kMaxE];
+    __shared__ int s_wave[16][3 + kNumTileHeights];
     __shared__ int s_hist[kFusedHistInts];
     const int e = threadIdx.x;
     int cnt = 0;
@@ -112,46 +127,54 @@ __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ id
         counts[e] = cnt;
     }
     s_cnt[e] = e < E ? cnt : -1;
-    int total;
-    const int off = block_excl_scan_1024(cnt, s_wave, &total);
-    if (e < E) offsets[e] = off;
-    if (e == 0) offsets[E] = total;
-    for (int q = 0; q < kNumTileHeights; ++q) {
-        const int bm = tile_height(q);
-        const int nt = e < E ? (cnt + bm - 1) / bm : 0;
-        const int p = block_excl_scan_1024(nt, s_wave, &total);
-        if (e < E) tileP[q * (E + 1) + e] = p;
-        if (e == 0) tileP[q * (E + 1) + E] = total;
+    // one pass of scans: offsets, the tile prefix tables of every tile height, the two size classes of every expert's rows
+    int nbig = cnt / kClsBigRows, last = cnt - nbig * kClsBigRows;
+    if (last > kClsSmallRows) { ++nbig; last = 0; }
+    constexpr int NV = 3 + kNumTileHeights;
+    int sc[NV], total[NV];
+    sc[0] = cnt;
+    sc[1] = e < E ? nbig : 0;
+    sc[2] = e < E && last > 0 ? 1 : 0;
+#pragma unroll
+    for (int q = 0; q < kNumTileHeights; ++q) sc[3 + q] = e < E ? (cnt + tile_height(q) - 1) / tile_height(q) : 0;
+    block_excl_scan_1024<NV>(sc, s_wave, total, E);
+    const int off = sc[0];
+    if (e < E) {
+        offsets[e] = off;
+        cls[kClsCountsBig * (E + 1) + e] = min(cnt, nbig * kClsBigRows);
+        cls[kClsCountsSmall * (E + 1) + e] = last;
+        cls[kClsOffsetsSmall * (E + 1) + e] = off + nbig * kClsBigRows;
+        cls[kClsPBig * (E + 1) + e] = sc[1];
+        cls[kClsPSmall * (E + 1) + e] = sc[2];
+#pragma unroll
+        for (int q = 0; q < kNumTileHeights; ++q) tileP[q * (E + 1) + e] = sc[3 + q];
     }
-    {   // the two size classes of every expert's rows
-        int nbig = cnt / kClsBigRows, last = cnt - nbig * kClsBigRows;
-        if (last > kClsSmallRows) { ++nbig; last = 0; }
-        if (e < E) {
-            cls[kClsCountsBig * (E + 1) + e] = min(cnt, nbig * kClsBigRows);
-            cls[kClsCountsSmall * (E + 1) + e] = last;
-            cls[kClsOffsetsSmall * (E + 1) + e] = off + nbig * kClsBigRows;
-        }
-        int p = block_excl_scan_1024(e < E ? nbig : 0, s_wave, &total);
-        if (e < E) cls[kClsPBig * (E + 1) + e] = p;
-        if (e == 0) cls[kClsPBig * (E + 1) + E] = total;
-        p = block_excl_scan_1024(e < E && last > 0 ? 1 : 0, s_wave, &total);
-        if (e < E) cls[kClsPSmall * (E + 1) + e] = p;
-        if (e == 0) cls[kClsPSmall * (E + 1) + E] = total;
+    if (e == 0) {
+        offsets[E] = total[0];
+        cls[kClsPBig * (E + 1) + E] = total[1];
+        cls[kClsPSmall * (E + 1) + E] = total[2];
+#pragma unroll
+        for (int q = 0; q < kNumTileHeights; ++q) tileP[q * (E + 1) + E] = total[3 + q];
     }
     __syncthreads();
     int rank = 0;                         // experts by descending count, ties by ascending id
     if (e < E) {
-        for (int o = 0; o < E; ++o) {
-            const int c = s_cnt[o];
-            rank += (c > cnt || (c == cnt && o < e)) ? 1 : 0;
+#pragma unroll 4
+        for (int o = 0; o < E; o += 4) {          // (the counts past E are -1: they never rank before an expert)
+            const int4 c = *(const int4*)&s_cnt[o];
+            rank += (c.x > cnt || (c.x == cnt && o < e)) ? 1 : 0;
+            rank += (c.y > cnt || (c.y == cnt && o + 1 < e)) ? 1 : 0;
+            rank += (c.z > cnt || (c.z == cnt && o + 2 < e)) ? 1 : 0;
+            rank += (c.w > cnt || (c.w == cnt && o + 3 < e)) ? 1 : 0;
         }
         order[rank] = e;
     }
     // Can the weight-gradient products give every XCD whole experts (expert of rank r to XCD r%8, every other
     // group of eight reversed)?  Then each operand panel is fetched by one XCD only.  Only if the reduction blocks
     // that each XCD would get stay within 10 % of the mean; the answer is control word kCtlByExpert.
-    __shared__ int s_xcd[8];
+    __shared__ int s_xcd[8], s_big;
     if (threadIdx.x < 8) s_xcd[threadIdx.x] = 0;
+    if (e < E && rank == 0) s_big = cnt;      // the largest expert
     __syncthreads();
     if (e < E) atomicAdd(&s_xcd[(rank >> 3) & 1 ? 7 - (rank & 7) : rank & 7], (cnt + 63) / 64);
     __syncthreads();
@@ -161,9 +184,7 @@ __global__ __launch_bounds__(1024) void plan_scan(const int32_t* __restrict__ id
         zeros[kCtlByExpert] = (E >= 8 && (long)mx * 80 <= (long)sum * 11) ? 1 : 0;
         // Strongly skewed sizes (largest expert above three times the mean): the weight-gradient products hand out
         // their tiles on demand instead of in fixed rounds; (control word kCtlSkewed).
-        int big = 0;
-        for (int i = 0; i < E; ++i) big = max(big, s_cnt[i]);
-        zeros[kCtlSkewed] = (E >= 2 && (long)big * E > 3 * M) ? 1 : 0;
+        zeros[kCtlSkewed] = (E >= 2 && (long)s_big * E > 3 * M) ? 1 : 0;
     }
 }
 
