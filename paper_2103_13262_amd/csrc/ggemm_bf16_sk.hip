@@ -806,6 +806,13 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         if (have)
             for (int i = tid; i < 2 * kActEntries; i += NT) w[i] = act_entry<KIND>(i);
     }
+    // Number of store instructions a wave issues in the epilogue of a full tile (bf16 output, nothing added to): they
+    // are the youngest memory operations when the next item's main loop is about to start, and the memory counter
+    // retires in order, so waiting until at most that many operations are outstanding means the item's first blocks
+    // (requested before the epilogue) have landed, without waiting for the stores to be acknowledged as well.
+    constexpr int kFullTileStores = TM * (TN / C::TNG) * 4 * (KIND == kRowsNN_GeLU ? 2 : 1);
+    static_assert(kFullTileStores < 64, "memory counter range");
+    bool stores_behind = false;              // the previous item ended with exactly those stores
     while (have) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -818,8 +825,10 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         const int nk = cur.kb1 - cur.kb0;
         if (nk > 0) {
             // The first blocks of this item were requested before the previous epilogue, whose own memory
-            // operations came later: wait for everything, then every wave may read ring slot 0.
-            wait_vmcnt<0>();
+            // operations came later: wait for everything but that epilogue's stores (where their number is known),
+            // then every wave may read ring slot 0.
+            if (stores_behind) wait_vmcnt<kFullTileStores>();
+            else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
             if (tm_act == TM) main_loop(std::true_type{}, nk);
             else main_loop(std::false_type{}, nk);   // tail tiles skip the 32-row blocks that hold no valid row
@@ -832,6 +841,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         if (have) start_item(cur);
         if (fin.owner) epilogue(fin);
         else store_partial();
+        stores_behind = fin.owner && fin.Mt == BM && fin.Nt == BN && !(KIND == kColsT && (g.out_f32 || g.accumulate));
     }
     if constexpr (KIND == kColsT) {
         if (dynamic && tid == 0) {       // the last workgroup to finish leaves the counters at zero for the next launch
