@@ -248,7 +248,7 @@ moe_status_t moe_scatter_backward_static(const moe_desc_t *desc, const moe_plan_
  * score_all = 0); "Xs" [M,d] scattered inputs, "dYs" [M,d], "dZ" [M,h], "dXs" [M,d] (dtype elements)
  * and "dl" [M] float, the gradient of the selected logits (valid after moe_backward).  Rows are in expert-contiguous order (row r holds
  * assignment perm[r]).  "gate_uncertified": [1 + N] int32, valid after moe_plan
- * for bf16 with 33 to 256 experts (score_all = balance_stats = 0): how many tokens the gate kernel that ranks
+ * for bf16 with 17 to 256 experts (score_all = balance_stats = 0): how many tokens the gate kernel that ranks
  * fp32 logits could not settle within its error bound (more than 16 candidates for the k places, or no finite bound) and
  * handed to the kernel that evaluates every logit in fp64, then their ids in no particular order.  "status": the int32 that
  * moe_check_status returns.  "clock": two int64 written by the last bf16 matrix-product launch,

@@ -159,7 +159,7 @@ template <typename Kern> static bool allow_dynamic_lds(Kern kern, int bytes)
 // ---- kernel launchers (each enqueues on `st`; operand shapes are validated by the callers) ----
 void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
                       float* topk_w, void* WgT, double* logits, double* lse, int32_t* gate_fail, hipStream_t st);
-// bf16 with 33 to 256 experts and no caller of the stored logits: fp32 logits on the bf16 matrix cores with a certified
+// bf16 with 17 to 256 experts and no caller of the stored logits: fp32 logits on the bf16 matrix cores with a certified
 // margin, fp64 for the k selected logits and for the tokens that cannot be certified (gate_fail: [1 + N] int32 scratch)
 void launch_gate_bf16(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx, float* topk_w,
                       void* WgT, int32_t* gate_fail, hipStream_t st);

@@ -1,4 +1,4 @@
-// Gate linear layer, top-k and the softmax over the k selected logits for bf16 inputs and 33 to 256 experts
+// Gate linear layer, top-k and the softmax over the k selected logits for bf16 inputs and 17 to 256 experts
 // (Algorithm 1: score = G(x), indices = ArgMax_k(score); the gate is one fully-connected layer, Section 5.2),
 // with the selection still that of exact arithmetic.
 //
@@ -428,7 +428,7 @@ static void launch_fast(const moe_desc_t& D, const u16* X, const u16* WgT, const
                        D.N, D.d, D.E, D.k, topk_idx, topk_w, fail);
 }
 
-// bf16, 33 to 256 experts, and no caller of the stored logits (scores over all experts, balance statistics).
+// bf16, 17 to 256 experts, and no caller of the stored logits (scores over all experts, balance statistics).
 void launch_gate_bf16(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx, float* topk_w,
                       void* WgT, int32_t* fail, hipStream_t st)
 {

@@ -542,7 +542,7 @@ __global__ __launch_bounds__(256) void gate_scores_all(const double* __restrict_
 void launch_gate_topk(const moe_desc_t& D, const void* X, const void* Wg, const float* bg, int32_t* topk_idx,
                       float* topk_w, void* WgT, double* logits, double* lse, int32_t* gate_fail, hipStream_t st)
 {
-    if (D.dtype == MOE_BF16 && D.E > 32 && D.E <= 256 && !logits) {
+    if (D.dtype == MOE_BF16 && D.E > 16 && D.E <= 256 && !logits) {
         launch_gate_bf16(D, X, Wg, bg, topk_idx, topk_w, WgT, gate_fail, st);
         return;
     }

@@ -32,6 +32,8 @@ CASES = [
     Workload("wide_gate_slabs_bf16", 300, 288, 64, 100, 2, "bf16", 0.0, 24),
     Workload("wide_gate_slabs_f32", 150, 160, 64, 70, 3, "f32", 0.0, 25),
     Workload("gate_24_experts_f32", 130, 96, 64, 24, 2, "f32", 0.0, 26),
+    Workload("gate_24_experts_bf16", 700, 96, 64, 24, 2, "bf16", 0.3, 38),
+    Workload("gate_32_experts_top4_bf16", 333, 160, 64, 32, 4, "bf16", 0.0, 39, 0.1),
     # experts with biases (b1, b2 ~ N(0, 0.1), about the size of the pre-activations); the second has empty experts
     # and tiles cut along the reduction
     Workload("biases_f32", 220, 96, 160, 5, 2, "f32", 0.0, 27, 0.1),
@@ -168,7 +170,7 @@ def test_engineered_ties_resolve_to_lowest_expert():
 
 
 def test_engineered_ties_with_many_experts_take_the_exact_path():
-    """33 to 256 experts in bf16: the gate ranks fp32 logits from the matrix cores and keeps as candidates whatever its
+    """17 to 256 experts in bf16: the gate ranks fp32 logits from the matrix cores and keeps as candidates whatever its
     error bound cannot separate from the k-th largest.  Equal gate columns and small-integer inputs (many exact ties)
     must resolve to the lower expert id; two columns that differ in one small element (logits a few 1e-3 apart at
     magnitude 10: inside the bound for some tokens, outside for others) must be ranked as in exact arithmetic; all-zero
