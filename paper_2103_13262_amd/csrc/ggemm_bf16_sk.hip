@@ -70,6 +70,15 @@ constexpr int kActHi = (127 + 3) << 7;          // bf16 bit pattern of 2^3
 constexpr int kActEntries = kActHi - kActLo;    // table entries per sign
 constexpr int kSpinLimit = 1 << 20;             // bounded wait for a partial sum (on the order of a second)
 
+// Results leave the chip as streaming (non-temporal) stores: none of them is read again by the launch that writes it,
+// and written the ordinary way they displace operand panels from the caches (measured: -2 % per step on the paper's
+// shape, -6 % with 64 or 256 experts; the weight gradients' stores matter most).
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+__device__ __forceinline__ void nt_store(uint4* p, const uint4 v)
+{
+    const u32x4_t w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, (u32x4_t*)p);
+}
 __device__ __forceinline__ int swap13(int c) { return (c & ~10) | ((c & 2) << 2) | ((c & 8) >> 2); }
 
 template <int BK> __device__ __forceinline__ int swz(int r)
@@ -417,6 +426,13 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
     // reduction indices past Kt are read from the zero page: always possible for the weight gradients (Kt = rows
     // of the expert), and for the other kinds only when a block is deeper than the 32 that divides every width
     constexpr bool KMASK = KIND == kColsT || BK > 32;
+    // Weight panels that one tile only will read (an expert's last piece; experts of at most 64 rows) are requested as
+    // streaming data, so that they do not push the panels other tiles share out of the caches.  Which products gain is
+    // measured, not derived (same-machine A/B runs): with many small experts the backward products (-9 % and -11 % per
+    // launch, the forward ones lose 7-10 %); for the last pieces all but dZ (C2: FC1, FC2 -4 %, dZ + 7 %).  Marking every
+    // operand load that way costs 11-25 % per step: the re-use of operands out of L2 is what the main loop lives on.
+    constexpr bool kStreamB = ((KIND == kRowsNT || KIND == kRowsNT_dGeLU) && BM == 64) ||
+                              (KIND != kColsT && KIND != kRowsNT_dGeLU && CLS == 2);
     // The loads are written as inline assembly so that the compiler does not serialise them against the LDS
     // reads of other ring slots; the ordering is enforced by the explicit vmcnt waits and barriers below.
     const unsigned lds_base = (unsigned)(uintptr_t)LDS_PTR(char, smem);
@@ -435,8 +451,12 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
             constexpr int i = l - C::LA;
             const u16* src = pb[i];
             if constexpr (KMASK) src = ((kb0 + li) * BK + kb[i] < Kt) ? src : zeros;
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(sA + C::A_BYTES + i * C::NW * 1024), "v"(src) : "memory");
+            if constexpr (kStreamB)
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                             :: "s"(sA + C::A_BYTES + i * C::NW * 1024), "v"(src) : "memory");
+            else
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(sA + C::A_BYTES + i * C::NW * 1024), "v"(src) : "memory");
             pb[i] += stepB;
         }
     };
@@ -728,7 +748,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
 #pragma unroll
                                 for (int t = 0; t < 8; ++t) xs[t] *= fac[t];
                                 const size_t o = it.c_off + (size_t)row * ldc + pcol;
-                                *(uint4*)((u16*)(KIND == kRowsNN_GeLU ? g.C2 : g.C) + o) = pack8(xs);
+                                nt_store((uint4*)((u16*)(KIND == kRowsNN_GeLU ? g.C2 : g.C) + o), pack8(xs));
                             }
                         }
                     }
@@ -743,7 +763,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
                         const size_t o = it.c_off + (size_t)row * ldc + pcol;
                         if constexpr (KIND == kRowsNN_GeLU) {
                             const uint4 zp = pack8(x);
-                            *(uint4*)((u16*)g.C + o) = zp;
+                            nt_store((uint4*)((u16*)g.C + o), zp);
                             const unsigned w[4] = {zp.x, zp.y, zp.z, zp.w};
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {   // H = z Phi(zb): z in fp32, Phi looked up at its bf16 rounding zb
@@ -779,14 +799,14 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
 #pragma unroll
                                     for (int t = 0; t < 8; ++t) x[t] += prev[t];
                                 }
-                                *Ch = pack8(x);
+                                nt_store(Ch, pack8(x));
                             }
                         } else {
                             size_t oo = o;
                             if constexpr (KIND == kRowsNN) {   // top-1: the row goes straight to its token's place in Y
                                 if (g.c_scatter) oo = (size_t)g.c_scatter[it.row0 + row] * ldc + (it.c_off - (size_t)it.row0 * ldc) + pcol;
                             }
-                            *(uint4*)((u16*)g.C + oo) = pack8(x);
+                            nt_store((uint4*)((u16*)g.C + oo), pack8(x));
                         }
                     }
                     cur = nxt;
