@@ -70,14 +70,18 @@ constexpr int kActHi = (127 + 3) << 7;          // bf16 bit pattern of 2^3
 constexpr int kActEntries = kActHi - kActLo;    // table entries per sign
 constexpr int kSpinLimit = 1 << 20;             // bounded wait for a partial sum (on the order of a second)
 
-// Results leave the chip as streaming (non-temporal) stores: none of them is read again by the launch that writes it,
-// and written the ordinary way they displace operand panels from the caches (measured: -2 % per step on the paper's
-// shape, -6 % with 64 or 256 experts; the weight gradients' stores matter most).
+// Results can leave the chip as streaming (non-temporal) stores: none of them is read again by the launch that writes
+// it, and written the ordinary way they displace operand panels from the caches.  Measured on one machine, A against
+// B: -2 % per step on the paper's shape (512 rows per expert), -6 % with 64 or 256 experts, the weight gradients'
+// stores mattering most; but +1.5 to +3 % with 2048 rows per expert and more, where every weight panel has many
+// readers and what counts is how fast the stores are taken.  The host decides per launch (GemmArgs::stream_out).
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
-__device__ __forceinline__ void nt_store(uint4* p, const uint4 v)
+__device__ __forceinline__ void store_out(uint4* p, const uint4 v, bool streaming)
 {
-    const u32x4_t w = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(w, (u32x4_t*)p);
+    if (streaming) {
+        const u32x4_t w = {v.x, v.y, v.z, v.w};
+        __builtin_nontemporal_store(w, (u32x4_t*)p);
+    } else *p = v;
 }
 __device__ __forceinline__ int swap13(int c) { return (c & ~10) | ((c & 2) << 2) | ((c & 8) >> 2); }
 
@@ -692,7 +696,8 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
     constexpr int TNG = C::TNG;                  // accumulator columns per pass through the patch
     constexpr int CPRW = TNG * 4;                // 8-column pieces per row of a column group
     static_assert(8 * CPRW <= 64 && TN % TNG == 0, "a slab of a column group is at most one piece per lane");
-    auto epilogue = [&](const Fin& it) {
+    auto epilogue = [&](const Fin& it, auto stream_tag) {
+        constexpr bool STREAM = decltype(stream_tag)::value;   // results as streaming stores (GemmArgs::stream_out)
         constexpr bool LOOKUP = C::TABLE;
         const int ldc = g.Nout;
         int lane_ = lane;
@@ -748,7 +753,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
 #pragma unroll
                                 for (int t = 0; t < 8; ++t) xs[t] *= fac[t];
                                 const size_t o = it.c_off + (size_t)row * ldc + pcol;
-                                nt_store((uint4*)((u16*)(KIND == kRowsNN_GeLU ? g.C2 : g.C) + o), pack8(xs));
+                                store_out((uint4*)((u16*)(KIND == kRowsNN_GeLU ? g.C2 : g.C) + o), pack8(xs), STREAM);
                             }
                         }
                     }
@@ -763,7 +768,7 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
                         const size_t o = it.c_off + (size_t)row * ldc + pcol;
                         if constexpr (KIND == kRowsNN_GeLU) {
                             const uint4 zp = pack8(x);
-                            nt_store((uint4*)((u16*)g.C + o), zp);
+                            store_out((uint4*)((u16*)g.C + o), zp, STREAM);
                             const unsigned w[4] = {zp.x, zp.y, zp.z, zp.w};
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {   // H = z Phi(zb): z in fp32, Phi looked up at its bf16 rounding zb
@@ -799,14 +804,14 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
 #pragma unroll
                                     for (int t = 0; t < 8; ++t) x[t] += prev[t];
                                 }
-                                nt_store(Ch, pack8(x));
+                                store_out(Ch, pack8(x), STREAM);
                             }
                         } else {
                             size_t oo = o;
                             if constexpr (KIND == kRowsNN) {   // top-1: the row goes straight to its token's place in Y
                                 if (g.c_scatter) oo = (size_t)g.c_scatter[it.row0 + row] * ldc + (it.c_off - (size_t)it.row0 * ldc) + pcol;
                             }
-                            nt_store((uint4*)((u16*)g.C + oo), pack8(x));
+                            store_out((uint4*)((u16*)g.C + oo), pack8(x), STREAM);
                         }
                     }
                     cur = nxt;
@@ -859,7 +864,10 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
         if (cur.kb0 > 0) add_predecessor();   // the blocks before kb0 were summed by the workgroup just below
         have = next_item(cur);
         if (have) start_item(cur);
-        if (fin.owner) epilogue(fin);
+        if (fin.owner) {
+            if (g.stream_out) epilogue(fin, std::true_type{});
+            else epilogue(fin, std::false_type{});
+        }
         else store_partial();
         stores_behind = fin.owner && fin.Mt == BM && fin.Nt == BN && !(KIND == kColsT && (g.out_f32 || g.accumulate));
     }
