@@ -41,8 +41,10 @@
 // The Gaussian factors of GeLU and GeLU' are looked up at the bf16 value zb that is stored as the
 // pre-activation, so they are functions of 16 bits: an LDS table indexed by the bit pattern (built from erfc /
 // exp at launch) gives Phi(zb) resp. Phi(zb) + zb phi(zb) exactly for 2^-11 <= |zb| < 8 and the nearest table
-// entry outside (|error| < 4e-4).  Forward: H = z Phi(zb) with z the fp32 accumulator; rounding z inside Phi
-// changes H by at most z^2 phi(z) 2^-9 < 6e-4, a fraction of H's own bf16 rounding.
+// entry outside (|error| < 4e-4).  Forward: H = z (Phi(zb) + (z - zb) phi(zb)) with z the fp32 accumulator: the
+// table's value at the rounded argument, carried back to z along the slope.  (Without the slope term H is off by up
+// to z^2 phi(z) 2^-9 < 6e-4, a fraction of H's own bf16 rounding, but enough to raise the error of the gate's
+// gradient by half in shapes with few tokens per expert.)
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
@@ -771,9 +773,15 @@ __device__ __forceinline__ void ggemm_sk_body(const GemmArgs& g, int ntm, int nt
                             store_out((uint4*)((u16*)g.C + o), zp, STREAM);
                             const unsigned w[4] = {zp.x, zp.y, zp.z, zp.w};
 #pragma unroll
-                            for (int t = 0; t < 4; ++t) {   // H = z Phi(zb): z in fp32, Phi looked up at its bf16 rounding zb
-                                fac[2 * t] = act[act_index(w[t])];
-                                fac[2 * t + 1] = act[act_index(w[t] >> 16)];
+                            for (int t = 0; t < 4; ++t) {
+                                // H = z Phi(z), z in fp32: Phi looked up at the bf16 rounding zb of z, plus the slope
+                                // phi(zb) times what the rounding took away (what is left is of second order, 2^-18)
+                                const float zlo = __uint_as_float(w[t] << 16), zhi = __uint_as_float(w[t] & 0xffff0000u);
+                                // (phi(zb) = 2^(-zb^2 log2(e) / 2) / sqrt(2 pi))
+                                fac[2 * t] = fmaf((x[2 * t] - zlo) * 0.39894228040143268f,
+                                                  __builtin_amdgcn_exp2f(zlo * zlo * -0.72134752044448170f), act[act_index(w[t])]);
+                                fac[2 * t + 1] = fmaf((x[2 * t + 1] - zhi) * 0.39894228040143268f,
+                                                      __builtin_amdgcn_exp2f(zhi * zhi * -0.72134752044448170f), act[act_index(w[t] >> 16)]);
                             }
 #pragma unroll
                             for (int t = 0; t < 8; ++t) xs[t] = x[t];

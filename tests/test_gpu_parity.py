@@ -61,6 +61,11 @@ CASES = [
     # Ys inside dw = <dY, Ys> alone moves it by 1e-1 of the vector's size.  Both are held to 1.5 times the ideal path.
     Workload("short_reduction_wide_dx_bf16", 1537, 2048, 256, 16, 1, "bf16", 1.2, 8025, 0.1, True),
     Workload("cancelling_gate_bias_bf16", 2503, 512, 256, 3, 2, "bf16", 2.0, 8022, 0.0, True),
+    # three shapes of a random sweep whose gate gradient was 1.6 times as far off as the ideal bf16 path's while the
+    # forward activation took its Gaussian factor at the rounded pre-activation without the slope term
+    Workload("few_tokens_gate_gradient_a_bf16", 8, 352, 2080, 17, 7, "bf16", 1.2, 7034, 0.0, True),
+    Workload("few_tokens_gate_gradient_b_bf16", 427, 416, 128, 65, 7, "bf16", 0.5, 7058, 0.0, True),
+    Workload("few_tokens_gate_gradient_c_bf16", 142, 448, 224, 31, 3, "bf16", 1.2, 7071, 0.1, False),
 ]
 
 
