@@ -31,3 +31,24 @@ def _shapes():
 @pytest.mark.parametrize("w", _shapes(), ids=lambda w: f"{w.name}-N{w.N}-d{w.d}-h{w.h}-E{w.E}-k{w.k}-{w.dtype}")
 def test_random_shape_matches_oracle(w):
     _full_check(w)
+
+
+def _draw(i):
+    """A wider draw (added with the bf16 gate kernel for 17 to 256 experts): expert counts on both sides of every
+    kernel's switching points (16 / 32 / 256 experts for the gate, 96 rows per expert for the tile shapes), one to
+    eight experts per token, up to 6000 tokens."""
+    g = np.random.default_rng([2103, 13262, i])
+    E = int(g.choice([1, 2, 4, 6, 8, 10, 15, 16, 17, 31, 32, 33, 48, 64, 65, 100, 130, 256, 260]))
+    k = int(g.integers(1, min(E, 8) + 1))
+    d = 32 * int(g.integers(1, 17))
+    h = 32 * int(g.choice([1, 2, 4, 7, 8, 16, 32, 64, 65, 128]))
+    budget = 2.5e8 / (d * h * k)
+    N = int(max(1, min(6000, g.integers(1, max(2, int(budget))))))
+    zipf = float(g.choice([0.0, 0.5, 1.2]))
+    dtype = "bf16" if i % 4 else "f32"
+    return Workload(f"random_{i}", N, d, h, E, k, dtype, zipf, 7100 + i, 0.1 if i % 2 else 0.0, i % 3 == 1)
+
+
+@pytest.mark.parametrize("i", range(32))
+def test_wider_random_shape_matches_oracle(i):
+    _full_check(_draw(i))
