@@ -315,6 +315,26 @@ def test_gpu_call_with_small_workspace_is_rejected():
     assert ei.value.status == B.MOE_ERR_WORKSPACE
 
 
+def test_a_wait_that_is_given_up_sets_the_status_word(monkeypatch):
+    """Tiles cut along the reduction hand partial sums from workgroup to workgroup; the wait for a predecessor's sum is
+    bounded, and a wait that runs out sets the workspace's status word instead of hanging.  MOE355_SPIN_LIMIT = -1
+    makes every such wait give up at once (every kernel still ends normally): moe_check_status must report it, and the
+    next step on the same workspace - whose plan step clears the word - must be clean and bit-equal to a first run."""
+    w = Workload("status", 300, 64, 4096, 3, 2, "bf16", 0.0, 81)       # FC2 reduces over 4096: its few tiles are cut
+    inputs = make_inputs(w)
+    first = GpuRun(w, inputs).run(backward=False)
+    assert first.status() == 0
+    y1 = first.Y.clone()
+    monkeypatch.setenv("MOE355_SPIN_LIMIT", "-1")
+    run = GpuRun(w, inputs).run(backward=False)
+    assert run.status() != 0
+    monkeypatch.delenv("MOE355_SPIN_LIMIT")
+    run.run(backward=False)
+    assert run.status() == 0
+    assert run.torch.equal(run.Y, y1)
+    run.check_guards()
+
+
 def test_step_captured_in_a_graph_replays_bit_for_bit():
     """The three calls enqueue kernels only (no host synchronisation, no memset nodes, no allocation after
     the first call), so a caller may capture them in a HIP graph: every replay, with eager work in between,
