@@ -222,7 +222,7 @@ struct GemmArgs {
     int32_t* dyn_counters;     // [9]: next tile of every XCD's list and the number of workgroups that have finished; zero between launches
     int whole_tiles;           // rows kinds: never cut a tile (another product in the same launch fills the idle workgroups)
     int on_demand;             // weight gradients: hand the tiles out from the counters whatever the sizes
-    int stream_out;            // bf16 products: results leave as streaming stores (set by the host for fewer than 1024 rows per expert)
+    int stream_out;            // bf16 products: results leave as streaming stores (set by the host when the experts' weights exceed the L2 caches)
     int spin_limit;            // polls of a "partial sum ready" flag before the wait is given up and the status word set (negative: at once)
     int out_f32;      // kColsT: C holds float (else the activation type)
     int accumulate;   // kColsT

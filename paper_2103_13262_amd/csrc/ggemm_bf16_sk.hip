@@ -74,9 +74,10 @@ constexpr int kSpinLimit = 1 << 20;             // bounded wait for a partial su
 
 // Results can leave the chip as streaming (non-temporal) stores: none of them is read again by the launch that writes
 // it, and written the ordinary way they displace operand panels from the caches.  Measured on one machine, A against
-// B: -2 % per step on the paper's shape (512 rows per expert), -6 % with 64 or 256 experts, the weight gradients'
-// stores mattering most; but +1.5 to +3 % with 2048 rows per expert and more, where every weight panel has many
-// readers and what counts is how fast the stores are taken.  The host decides per launch (GemmArgs::stream_out).
+// B: -2 % per step on the paper's shape (134 MB of weights per product), -6 % with 64 or 256 experts, the weight
+// gradients' stores mattering most; but +1.5 to +3 % with 1, 2 or 4 experts of that width (8 to 32 MB), whose weights
+// stay in the 32 MB of L2 whatever the stores do, so that what counts is how fast the stores are taken.  The host
+// decides per launch (GemmArgs::stream_out): streaming when one product's weights exceed 48 MB.
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
 __device__ __forceinline__ void store_out(uint4* p, const uint4 v, bool streaming)
 {

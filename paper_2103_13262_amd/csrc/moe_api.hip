@@ -309,7 +309,7 @@ moe_status_t moe_forward(const moe_desc_t* desc, const moe_plan_t* plan, const v
     // scatter of Section 4 done on the fly (moe_backward writes Xs when the weight gradient needs it).
     GemmArgs a{};
     a.M = (long)D.N * D.k;
-    a.stream_out = a.M < 1024L * D.E;   // (measured: pays below about a thousand rows per expert, costs above two thousand)
+    a.stream_out = (size_t)D.E * D.d * D.h * 2 > ((size_t)48 << 20);   // (the experts' weights do not fit the L2 caches: see store_out)
     a.E = D.E;
     a.counts = plan->counts;
     a.offsets = plan->offsets;
@@ -375,7 +375,7 @@ moe_status_t moe_backward(const moe_desc_t* desc, const moe_plan_t* plan, const 
 
     GemmArgs a{};
     a.M = (long)D.N * D.k;
-    a.stream_out = a.M < 1024L * D.E;   // (measured: pays below about a thousand rows per expert, costs above two thousand)
+    a.stream_out = (size_t)D.E * D.d * D.h * 2 > ((size_t)48 << 20);   // (the experts' weights do not fit the L2 caches: see store_out)
     a.E = D.E;
     a.counts = plan->counts;
     a.offsets = plan->offsets;
