@@ -6,15 +6,16 @@
 // result through the k selected ones.  So:
 //  (1) all logits in fp32 on the bf16 matrix cores (products of two bf16 values are exact in fp32; only the summation
 //      rounds), together with the same product of the absolute values, S[t,e] = sum_i |x_i| |w_ie| + |b_e|, which
-//      bounds the rounding error of a sum of d + 1 terms in ANY order by (d + 1) 2^-24 S;
+//      bounds the rounding error of a sum of d + 1 terms in ANY order by (d + 1) 2^-24 S (the kernel takes four
+//      times that, and for S the largest value among the workgroup's tokens and experts);
 //  (2) per token the k-th largest fp32 logit v_k (k rounds of a wavefront-wide argmax, four tokens interleaved);
 //      an expert can only be among the exact k largest if its fp32 logit is at least v_k minus twice the bound: these
 //      CANDIDATES are usually just the k largest, sometimes one or two more (near-ties, equal gate columns);
 //  (3) the candidates' logits again in fp64 (16 lanes per token and candidate, each a slice of the features, one fixed
 //      butterfly: equal gate columns give equal sums), the k largest with ties to the lower expert id are the
 //      selection, their softmax the scores;
-//  (4) a token with more than 16 candidates (e.g. an all-zero row: every logit equal) goes on a list for a second
-//      kernel that evaluates all E logits in fp64.
+//  (4) a token with more than 16 candidates (e.g. an all-zero row: every logit equal), or of a workgroup whose S is not
+//      finite, goes on a list for a second kernel that evaluates all E logits in fp64.
 //
 // Kernels: gate_prep (transposed gate matrix [E][d], so that an expert's weights are contiguous; clears the list's
 // counter), gate_bf16_kernel<G> (32 tokens per workgroup of 8 wavefronts, G = 64, 128 or 256 expert columns; a
